@@ -1,0 +1,375 @@
+"""Pins for the CPU oracle: every check here compares oracle/ against something other than
+itself (exact rational arithmetic written a different way, closed forms, hand-worked values
+from the equations of Sec. 2.1 / 2.2, scipy.ndimage and torch routines, identities).
+None of these tests needs a GPU."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_06154_amd import workloads as wl
+
+DTYPES = [np.float32, np.float64]
+
+
+# ---------------------------------------------------------------------------------------
+# Independent evaluators (tap-list driven, exact rationals) -- not the oracle's loop nest.
+# ---------------------------------------------------------------------------------------
+
+def _fetch(field, coords, boundary):
+    """field indexed [z][y][x]; coords (x, y, z) possibly outside."""
+    D, H, W = field.shape
+    x, y, z = coords
+    if boundary == "clamp":
+        x = min(max(x, 0), W - 1)
+        y = min(max(y, 0), H - 1)
+        z = min(max(z, 0), D - 1)
+    elif not (0 <= x < W and 0 <= y < H and 0 <= z < D):
+        return Fraction(0)
+    return Fraction(float(field[z, y, x]))
+
+
+def exact_taps(field3, taps, boundary):
+    """taps: list of (dx, dy, dz, coef).  Returns an object array of Fractions."""
+    D, H, W = field3.shape
+    out = np.empty((D, H, W), dtype=object)
+    for z in range(D):
+        for y in range(H):
+            for x in range(W):
+                acc = Fraction(0)
+                for dx, dy, dz, c in taps:
+                    acc += Fraction(float(c)) * _fetch(field3, (x + dx, y + dy, z + dz), boundary)
+                out[z, y, x] = acc
+    return out
+
+
+def round_to(exact, dtype):
+    f = np.vectorize(lambda q: float(q), otypes=[np.float64])(exact)
+    return f.astype(dtype)
+
+
+def assert_within_ulp(got, exact, dtype, ulps=1.0):
+    want = round_to(exact, dtype)
+    tol = ulps * np.spacing(np.abs(want).astype(dtype)).astype(np.float64)
+    tol = np.maximum(tol, np.finfo(dtype).tiny)
+    assert got.dtype == np.dtype(dtype)
+    assert np.all(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol)
+
+
+def filter_taps(filt, ax, ay):
+    N, M = filt.shape
+    return [(m - ax, n - ay, 0, filt[n, m]) for n in range(N) for m in range(M)]
+
+
+def box_taps(coef3):
+    nz, ny, nx = coef3.shape
+    rz, ry, rx = nz // 2, ny // 2, nx // 2
+    return [(i - rx, j - ry, k - rz, coef3[k, j, i])
+            for k in range(nz) for j in range(ny) for i in range(nx) if coef3[k, j, i] != 0]
+
+
+def rng_field(shape, seed, dtype, lo=-1.0, hi=1.0):
+    return wl.uniform_field(shape, lo, hi, seed, dtype)
+
+
+# ---------------------------------------------------------------------------------------
+# 1. Exact brute force on tiny grids (grids smaller than the filter, even sizes, M != N,
+#    explicit anchors, both boundary rules, both precisions).
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("boundary", ["zero", "clamp"])
+@pytest.mark.parametrize("W,H,M,N,anchor", [
+    (7, 5, 3, 3, None), (7, 5, 2, 2, None), (6, 4, 4, 3, None), (5, 6, 3, 11, None), (9, 3, 11, 3, None),
+    (4, 3, 6, 5, None), (7, 5, 3, 2, (0, 0)), (7, 5, 4, 3, (3, 2)), (1, 1, 3, 3, None), (8, 1, 3, 1, None),
+])
+def test_conv2d_exact_bruteforce(dtype, boundary, W, H, M, N, anchor):
+    img = rng_field((H, W), 11, dtype)
+    filt = wl.seeded_filter(M, N, 12, dtype)
+    ax, ay = (M // 2, N // 2) if anchor is None else anchor
+    got = oracle.conv2d(img, filt, boundary, anchor)
+    exact = exact_taps(img[None], filter_taps(filt, ax, ay), boundary)[0]
+    assert_within_ulp(got, exact, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("boundary", ["zero", "clamp"])
+@pytest.mark.parametrize("shape,mask", [
+    ((5, 7), wl.mask_star(1, 1)[0]), ((5, 7), wl.mask_box(2, 1)[0]), ((3, 4), wl.mask_star(4, 4)[0]),
+    ((6, 5), wl.mask_star(1, 2)[0]),
+    ((4, 3, 5), wl.mask_star(1, 1, 1)), ((4, 3, 5), wl.mask_box(1, 1, 1)), ((3, 4, 4), wl.mask_faces_edges()),
+    ((2, 3, 9), wl.mask_star(4, 1, 2)), ((5, 2, 3), wl.mask_box(1, 2, 1)),
+])
+def test_stencil_exact_bruteforce(dtype, boundary, shape, mask):
+    fld = rng_field(shape, 21, dtype)
+    mask3 = mask if mask.ndim == 3 else mask[None]
+    coef3 = wl.seeded_coefficients(mask3, 22, dtype, -1.0, 1.0, normalise=False)
+    coef = coef3 if len(shape) == 3 else coef3[0]
+    got = oracle.stencil(fld, coef, boundary)
+    f3 = fld if fld.ndim == 3 else fld[None]
+    exact = exact_taps(f3, box_taps(coef3), boundary)
+    exact = exact if fld.ndim == 3 else exact[0]
+    assert_within_ulp(got, exact, dtype)
+
+
+# ---------------------------------------------------------------------------------------
+# 2. Hand-worked values straight from the equations.
+# ---------------------------------------------------------------------------------------
+
+def test_five_point_equation_by_hand():
+    """Sec. 2.2: s'(x,y) = s(x-1,y)West + s(x,y-1)North + s(x,y)Current + s(x,y+1)South + s(x+1,y)East."""
+    s = np.array([[1, 2, 3], [4, 5, 6], [7, 8, 9]], dtype=np.float64)   # s[y][x]
+    West, North, Current, South, East = 1.0, 2.0, 3.0, 4.0, 5.0
+    coef = np.array([[0, North, 0], [West, Current, East], [0, South, 0]], dtype=np.float64)
+    out = oracle.stencil(s, coef, "zero")
+    # centre (x=1,y=1): 4*1 + 2*2 + 5*3 + 8*4 + 6*5
+    assert out[1, 1] == 85.0
+    # corner (x=0,y=0), zero padding: 0*1 + 0*2 + 1*3 + 4*4 + 2*5
+    assert out[0, 0] == 29.0
+    # edge (x=2,y=1): 5*1 + 3*2 + 6*3 + 9*4 + 0*5
+    assert out[1, 2] == 65.0
+    outc = oracle.stencil(s, coef, "clamp")
+    # corner with clamp: west->s(0,0)=1, north->1 : 1*1 + 1*2 + 1*3 + 4*4 + 2*5
+    assert outc[0, 0] == 32.0
+    assert outc[1, 1] == 85.0
+
+
+def test_seven_point_above_below_by_hand():
+    """Sec. 2.2 last paragraph: Above multiplies s(x,y,z-1), Below s(x,y,z+1)."""
+    s = np.arange(27, dtype=np.float64).reshape(3, 3, 3)                # s[z][y][x]
+    coef = np.zeros((3, 3, 3))
+    coef[0, 1, 1] = 10.0     # Above: dz = -1
+    coef[2, 1, 1] = 100.0    # Below: dz = +1
+    coef[1, 1, 1] = 1.0
+    out = oracle.stencil(s, coef, "zero")
+    assert out[1, 1, 1] == 13.0 + 10.0 * 4.0 + 100.0 * 22.0
+    assert out[0, 1, 1] == 4.0 + 100.0 * 13.0            # nothing above the first plane
+    assert out[2, 0, 2] == 20.0 + 10.0 * 11.0
+
+
+def test_one_dimensional_example():
+    """Sec. 3.5: three-tap 1D filter, b_i = a_{i-1} f_0 + a_i f_1 + a_{i+1} f_2."""
+    a = np.array([[3, 1, 4, 1, 5, 9, 2, 6]], dtype=np.float32)
+    f = np.array([[2, 3, 5]], dtype=np.float32)
+    b = oracle.conv2d(a, f, "zero")
+    want = [3 * 3 + 1 * 5, 3 * 2 + 1 * 3 + 4 * 5, 1 * 2 + 4 * 3 + 1 * 5, 4 * 2 + 1 * 3 + 5 * 5,
+            1 * 2 + 5 * 3 + 9 * 5, 5 * 2 + 9 * 3 + 2 * 5, 9 * 2 + 2 * 3 + 6 * 5, 2 * 2 + 6 * 3]
+    assert b[0].tolist() == [float(v) for v in want]
+
+
+def test_true_convolution_is_correlation_with_flipped_filter():
+    """Sec. 2.1's canonical form (f*w)(x,y) = sum_{s,t} f(x-s, y-t) w(s,t), evaluated literally,
+    equals the oracle (which does not flip, like Listing 1) called with the filter flipped."""
+    dtype = np.float64
+    H, W, M, N = 6, 7, 3, 5
+    img = np.round(rng_field((H, W), 31, dtype) * 16)        # small integers: exact arithmetic
+    w = np.round(wl.seeded_filter(M, N, 32, dtype) * 8)
+    a, c = -(M // 2), -(N // 2)                               # s in [a, a+M), t in [c, c+N)
+    literal = np.zeros((H, W))
+    for y in range(H):
+        for x in range(W):
+            acc = 0.0
+            for t in range(c, c + N):
+                for s in range(a, a + M):
+                    xs, yt = x - s, y - t
+                    if 0 <= xs < W and 0 <= yt < H:
+                        acc += img[yt, xs] * w[t - c, s - a]
+            literal[y, x] = acc
+    got = oracle.conv2d(img, np.ascontiguousarray(w[::-1, ::-1]), "zero", anchor=(M - 1 - M // 2, N - 1 - N // 2))
+    assert np.array_equal(got, literal)
+
+
+# ---------------------------------------------------------------------------------------
+# 3. Delta, constant and linear inputs.
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_delta_reproduces_filter_point_reflected(dtype):
+    M, N, W, H = 5, 4, 16, 13
+    ax, ay = M // 2, N // 2
+    filt = wl.seeded_filter(M, N, 41, dtype)
+    x0, y0 = 8, 6
+    img = np.zeros((H, W), dtype=dtype)
+    img[y0, x0] = 1
+    out = oracle.conv2d(img, filt, "zero")
+    want = np.zeros_like(img)
+    for n in range(N):
+        for m in range(M):
+            want[y0 + ay - n, x0 + ax - m] = filt[n, m]
+    assert np.array_equal(out, want)
+
+
+def test_delta_at_corner_zero_cuts_and_clamp_sums():
+    dtype = np.float64
+    filt = (np.arange(9, dtype=dtype).reshape(3, 3) + 1)          # w[n][m] = 3n+m+1
+    img = np.zeros((5, 6), dtype=dtype)
+    img[0, 0] = 1
+    z = oracle.conv2d(img, filt, "zero")
+    # out[y][x] = w[n][m] with x+m-1 == 0, y+n-1 == 0 -> m = 1-x, n = 1-y
+    assert z[0, 0] == filt[1, 1] and z[0, 1] == filt[1, 0] and z[1, 0] == filt[0, 1] and z[1, 1] == filt[0, 0]
+    assert np.count_nonzero(z) == 4
+    c = oracle.conv2d(img, filt, "clamp")
+    # at (0,0) every tap with x+m-1 <= 0 and y+n-1 <= 0 clamps onto the delta: m in {0,1}, n in {0,1}
+    assert c[0, 0] == filt[0, 0] + filt[0, 1] + filt[1, 0] + filt[1, 1]
+    assert c[0, 1] == filt[0, 0] + filt[1, 0]      # x=1: only m=0 reaches column 0; n in {0,1}
+    assert c[1, 0] == filt[0, 0] + filt[0, 1]
+    assert c[1, 1] == filt[0, 0]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_constant_field_sums_weights(dtype):
+    """Dyadic constants and weights make every sum exact.  Zero padding: a point near the edge
+    gets the sum of the taps that still fall inside, which exposes anchor and orientation."""
+    M, N, W, H = 4, 3, 9, 8
+    ax, ay = M // 2, N // 2
+    filt = (np.round(wl.seeded_filter(M, N, 51, np.float64) * 64) / 64).astype(dtype)
+    c0 = dtype(0.375)
+    img = np.full((H, W), c0, dtype=dtype)
+    clamp = oracle.conv2d(img, filt, "clamp")
+    assert np.all(clamp == dtype(c0 * filt.astype(np.float64).sum()))
+    zero = oracle.conv2d(img, filt, "zero")
+    for y in range(H):
+        for x in range(W):
+            inside = sum(float(filt[n, m]) for n in range(N) for m in range(M)
+                         if 0 <= x + m - ax < W and 0 <= y + n - ay < H)
+            assert zero[y, x] == dtype(float(c0) * inside)
+
+
+@pytest.mark.parametrize("dims", [2, 3])
+def test_linear_field_preserved_by_symmetric_unit_sum_stencil(dims):
+    dtype = np.float64
+    r = 2
+    coef = wl.seeded_symmetric_star(r, dims, 61, dtype)
+    n = 12
+    if dims == 2:
+        yy, xx = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+        fld = (0.5 * xx - 0.25 * yy + 3).astype(dtype)
+        out = oracle.stencil(fld, coef[0], "zero")
+        sl = (slice(r, n - r),) * 2
+    else:
+        zz, yy, xx = np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij")
+        fld = (0.5 * xx - 0.25 * yy + 2.0 * zz + 3).astype(dtype)
+        out = oracle.stencil(fld, coef, "zero")
+        sl = (slice(r, n - r),) * 3
+    assert np.allclose(out[sl], fld[sl], rtol=0, atol=1e-13)
+    assert not np.allclose(out, fld, rtol=0, atol=1e-3)      # the zero-padded rim does change
+
+
+# ---------------------------------------------------------------------------------------
+# 4. Library routines as special cases.
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("boundary,mode", [("zero", "constant"), ("clamp", "nearest")])
+@pytest.mark.parametrize("M,N", [(3, 3), (5, 5), (2, 2), (4, 6), (3, 11), (11, 3), (20, 20)])
+def test_conv2d_matches_scipy_correlate(boundary, mode, M, N):
+    from scipy import ndimage
+    img = rng_field((37, 45), 71, np.float64)
+    filt = wl.seeded_filter(M, N, 72, np.float64)
+    got = oracle.conv2d(img, filt, boundary)
+    want = ndimage.correlate(img, filt, mode=mode, cval=0.0, origin=0)
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("boundary,mode", [("zero", "constant"), ("clamp", "nearest")])
+def test_stencil3d_matches_scipy_correlate(boundary, mode):
+    from scipy import ndimage
+    fld = rng_field((9, 11, 13), 73, np.float64)
+    for mask in (wl.mask_star(1, 1, 1), wl.mask_box(1, 1, 1), wl.mask_faces_edges(), wl.mask_star(4, 4, 4),
+                 wl.mask_box(2, 1, 0)):
+        coef = wl.seeded_coefficients(mask, 74, np.float64, -1.0, 1.0, normalise=False)
+        got = oracle.stencil(fld, coef, boundary)
+        want = ndimage.correlate(fld, coef, mode=mode, cval=0.0, origin=0)
+        assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("boundary,pad_mode", [("zero", "constant"), ("clamp", "replicate")])
+@pytest.mark.parametrize("anchor", [None, (0, 0), (3, 1)])
+def test_conv2d_matches_torch_conv2d(boundary, pad_mode, anchor):
+    import torch
+    import torch.nn.functional as F
+    M, N = 4, 3
+    ax, ay = (M // 2, N // 2) if anchor is None else anchor
+    img = rng_field((19, 23), 75, np.float32)
+    filt = wl.seeded_filter(M, N, 76, np.float32)
+    got = oracle.conv2d(img, filt, boundary, anchor)
+    t = torch.from_numpy(img.astype(np.float64))[None, None]
+    t = F.pad(t, (ax, M - 1 - ax, ay, N - 1 - ay), mode=pad_mode)
+    want = F.conv2d(t, torch.from_numpy(filt.astype(np.float64))[None, None])[0, 0].numpy()
+    assert np.allclose(got, want, rtol=0, atol=2e-6)
+
+
+def test_stencil3d_matches_torch_conv3d():
+    import torch
+    import torch.nn.functional as F
+    fld = rng_field((6, 7, 8), 77, np.float64)
+    coef = wl.seeded_coefficients(wl.mask_box(2, 1, 1), 78, np.float64, -1.0, 1.0, normalise=False)
+    got = oracle.stencil(fld, coef, "zero")
+    want = F.conv3d(torch.from_numpy(fld)[None, None], torch.from_numpy(coef)[None, None],
+                    padding=(1, 1, 2))[0, 0].numpy()
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_separable_filter_equals_row_then_column_pass():
+    dtype = np.float64
+    u = wl.uniform_at(np.arange(5), -1, 1, 81, dtype)       # vertical factor (N=5)
+    v = wl.uniform_at(np.arange(7), -1, 1, 82, dtype)       # horizontal factor (M=7)
+    img = rng_field((21, 26), 83, dtype)
+    full = oracle.conv2d(img, np.outer(u, v), "zero")
+    rows = oracle.conv2d(img, v[None, :], "zero")
+    both = oracle.conv2d(rows, u[:, None], "zero")
+    assert np.allclose(full, both, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# 5. Iteration (Jacobi, two buffers).
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_iterate_identities(dtype):
+    fld = rng_field((14, 17), 91, dtype)
+    coef = wl.seeded_coefficients(wl.mask_box(2, 2), 92, dtype)[0]
+    assert np.array_equal(oracle.iterate(fld, coef, 0), fld)
+    assert np.array_equal(oracle.iterate(fld, coef, 1), oracle.stencil(fld, coef, "zero"))
+    five = oracle.iterate(fld, coef, 5)
+    assert np.array_equal(oracle.iterate(oracle.iterate(fld, coef, 2), coef, 3), five)
+    # explicit repeated single sweeps, odd and even step counts (buffer parity)
+    cur = fld
+    for _ in range(4):
+        cur = oracle.stencil(cur, coef, "zero")
+    assert np.array_equal(oracle.iterate(fld, coef, 4), cur)
+
+
+def test_iterate_is_a_max_norm_contraction_and_linear():
+    dtype = np.float64
+    coef = wl.seeded_coefficients(wl.mask_star(1, 1, 1), 93, dtype)        # w >= 0, sum 1
+    u = rng_field((6, 7, 8), 94, dtype)
+    v = rng_field((6, 7, 8), 95, dtype)
+    prev = np.abs(u).max()
+    for t in range(1, 5):
+        cur = np.abs(oracle.iterate(u, coef, t)).max()
+        assert cur <= prev + 1e-15
+        prev = cur
+    lhs = oracle.iterate(2.0 * u - 0.5 * v, coef, 3)
+    rhs = 2.0 * oracle.iterate(u, coef, 3) - 0.5 * oracle.iterate(v, coef, 3)
+    assert np.allclose(lhs, rhs, rtol=0, atol=1e-14)
+
+
+def test_iterate_3d_matches_repeated_scipy():
+    from scipy import ndimage
+    fld = rng_field((7, 8, 9), 96, np.float64)
+    coef = wl.seeded_coefficients(wl.mask_faces_edges(), 97, np.float64)
+    want = fld
+    for _ in range(3):
+        want = ndimage.correlate(want, coef, mode="constant", cval=0.0)
+    assert np.allclose(oracle.iterate(fld, coef, 3), want, rtol=0, atol=1e-13)
+
+
+def test_zero_coefficient_means_no_tap():
+    """An exactly-zero coefficient is skipped, so a non-finite neighbour under it does not leak."""
+    fld = np.ones((5, 5), dtype=np.float64)
+    fld[2, 1] = np.inf
+    coef = np.array([[0, 1, 0], [0, 1, 1], [0, 1, 0]], dtype=np.float64)    # no West tap
+    out = oracle.stencil(fld, coef, "zero")
+    assert out[2, 2] == 4.0
+    assert np.isinf(out[2, 1])
