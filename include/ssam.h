@@ -1,0 +1,110 @@
+/* ssam.h -- C ABI of the MI355X (gfx950) software-systolic structured-grid library.
+ *
+ * The library evaluates regular structured-grid kernels
+ *        out[p] = sum_k  w_k * in[p + offset_k]
+ * -- dense 2D filters (paper Sec. 2.1, evaluated as in Listing 1), 2D and 3D stencils
+ * (Sec. 2.2) and their Jacobi iteration -- with the paper's execution model (Sec. 3.3,
+ * Sec. 4): a register cache per lane, partial sums passed between the lanes of a
+ * wavefront, overlapped blocking; re-designed for 64-lane CDNA4 wavefronts.
+ *
+ * Conventions common to every entry point
+ *   - Grids are dense, row-major, x fastest:  index = (z*H + y)*W + x.  No pitch.
+ *   - `d_*` arguments are DEVICE pointers owned by the caller; the library neither frees
+ *     nor retains them.  They must hold W*H(*D) elements of the type named by `dtype`.
+ *   - `h_*` arguments are HOST pointers, read synchronously during the call (they may be
+ *     freed or changed as soon as the call returns), in the type named by `dtype`.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and the call returns without synchronising.  Launches on one stream are
+ *     ordered; the caller synchronises before reading results.
+ *   - The return value is the only error channel (an ssam_status).  All argument checks
+ *     happen before any GPU call, so a bad call never touches the device.
+ *   - Boundary rule: a read outside the grid gives 0 (SSAM_BOUNDARY_ZERO) or the value of
+ *     the nearest grid point, every coordinate clamped on its own (SSAM_BOUNDARY_CLAMP).
+ *     The paper does not state a rule; these are the two its comparison libraries use.
+ *   - Results are deterministic run to run (no atomics); the order of additions differs
+ *     from a sequential sum, so results agree with a reference to rounding, not bitwise.
+ *   - Thread safety: calls may be made from several host threads on different streams.
+ */
+#ifndef SSAM_H_
+#define SSAM_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SSAM_OK = 0,
+    SSAM_ERR_NULL = 1,   /* a required pointer is NULL                                    */
+    SSAM_ERR_DIM = 2,    /* W, H or D not positive, or the grid exceeds 2^31-1 elements   */
+    SSAM_ERR_SHAPE = 3,  /* filter / radius not positive, anchor outside the filter, or
+                            larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0      */
+    SSAM_ERR_ENUM = 4,   /* unknown dtype or boundary value                               */
+    SSAM_ERR_ALIAS = 5,  /* input and output buffers overlap                              */
+    SSAM_ERR_HIP = 6     /* a HIP runtime call failed (no device, launch failure)         */
+} ssam_status;
+
+typedef enum { SSAM_F32 = 0, SSAM_F64 = 1 } ssam_dtype;
+typedef enum { SSAM_BOUNDARY_ZERO = 0, SSAM_BOUNDARY_CLAMP = 1 } ssam_boundary;
+
+#define SSAM_MAX_FILTER 32   /* largest filter width or height accepted by ssam_conv2d   */
+#define SSAM_MAX_RADIUS 8    /* largest stencil radius per axis                          */
+
+/* 2D filter (paper Sec. 2.1; Listing 1 evaluates it without flipping the filter):
+ *     out[y][x] = sum_{n<N} sum_{m<M}  h_filter[n*M + m] * IN(x + m - ax, y + n - ay)
+ * M is the filter width (x extent), N its height (y extent), as in the paper.  (ax, ay) is
+ * the filter element placed on the output point; pass -1 for the default M/2, N/2 (integer
+ * division).  The canonical flipped convolution of Sec. 2.1 is obtained by passing the
+ * filter reversed in both axes.  d_in and d_out must not overlap. */
+int ssam_conv2d(const void *d_in, void *d_out, int W, int H,
+                const void *h_filter, int M, int N, int ax, int ay,
+                int boundary, int dtype, void *hip_stream);
+
+/* One sweep of a 2D stencil (paper Sec. 2.2, Listing 2):
+ *     out[y][x] = sum_{|dy|<=ry} sum_{|dx|<=rx}  h_coef[(dy+ry)*(2rx+1) + (dx+rx)] * IN(x+dx, y+dy)
+ * h_coef is the dense (2ry+1) x (2rx+1) coefficient box; an exactly-zero entry means that
+ * offset is not part of the stencil (star shapes are boxes with zeros).  In the paper's
+ * five-point naming: West = (dx,dy)=(-1,0), North = (0,-1), South = (0,+1), East = (+1,0). */
+int ssam_stencil2d(const void *d_in, void *d_out, int W, int H,
+                   const void *h_coef, int rx, int ry,
+                   int boundary, int dtype, void *hip_stream);
+
+/* One sweep of a 3D stencil (paper Sec. 2.2 last paragraph, Sec. 4.9):
+ *     out[z][y][x] = sum  h_coef[((dz+rz)*(2ry+1) + (dy+ry))*(2rx+1) + (dx+rx)] * IN(x+dx, y+dy, z+dz)
+ * with the same zero-means-no-tap rule; Above = dz -1, Below = dz +1. */
+int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
+                   const void *h_coef, int rx, int ry, int rz,
+                   int boundary, int dtype, void *hip_stream);
+
+/* `steps` Jacobi sweeps (paper Sec. 2.2: s_{i+1} computed from s_i) with two buffers:
+ * sweep 0 reads d_a and writes d_b, sweep 1 reads d_b and writes d_a, and so on; every grid
+ * point is updated each sweep, the boundary rule supplying reads outside the grid.  D == 1
+ * with rz == 0 is the 2D case.  *d_result (host location, may be NULL) receives the buffer
+ * that holds the field after `steps` sweeps: d_a for even counts (steps == 0 does nothing),
+ * d_b for odd counts.  Both buffers are overwritten when steps >= 2.  No host
+ * synchronisation happens between sweeps. */
+int ssam_stencil_iterate(void *d_a, void *d_b, int W, int H, int D,
+                         const void *h_coef, int rx, int ry, int rz,
+                         int boundary, int dtype, int steps,
+                         void *hip_stream, void **d_result);
+
+/* Human-readable name of an ssam_status value (static storage; never NULL). */
+const char *ssam_status_string(int status);
+
+/* Tuning override for experiments and benchmarks (not needed for correct use): sets a named
+ * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
+ * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic".  value < 0 restores the
+ * built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
+int ssam_set_tuning(const char *name, int value);
+
+/* Describes the kernel instance the dispatcher would pick for a problem, without launching:
+ * writes a NUL-terminated description ("conv2d_f32_M3N3_v4p8 grid=... block=...") into buf
+ * (at most buflen bytes).  Arguments as for the matching entry point; kind 0 = conv2d,
+ * 1 = stencil2d, 2 = stencil3d.  For conv2d pass M,N in rx,ry... see ssam_describe docs in
+ * the Python binding.  Runs entirely on the host. */
+int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
+                  int boundary, int dtype, char *buf, int buflen);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSAM_H_ */

@@ -1,0 +1,435 @@
+// C ABI of the library: argument validation, shape classification, dispatch to the compiled
+// register-cache instances, the direct fallback kernel for every other shape, Jacobi
+// ping-pong, tuning overrides.  All validation happens before the first HIP call.
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+#include <string>
+
+#include "ssam_device.h"
+#include "ssam_host.h"
+
+namespace ssam {
+
+std::vector<Instance2D>& registry2d()
+{
+    static std::vector<Instance2D> r;
+    return r;
+}
+std::vector<Instance3D>& registry3d()
+{
+    static std::vector<Instance3D> r;
+    return r;
+}
+
+namespace {
+
+std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
+    g_force_generic{-1};
+
+Tuning current_tuning()
+{
+    Tuning t;
+    t.rows_per_wave = g_rows_per_wave.load();
+    t.valid_lanes = g_valid_lanes.load();
+    t.planes_per_wave = g_planes_per_wave.load();
+    t.xcd_remap = g_xcd_remap.load();
+    t.force_generic = g_force_generic.load();
+    return t;
+}
+
+// ---- direct fallback kernel -------------------------------------------------------------
+// One output point per thread, taps read straight from global memory (cached).  It keeps the
+// ABI total: any filter or stencil shape without a compiled register-cache instance runs
+// here.  Coefficients travel in the kernel argument block, dense [K][N][M] or, for star
+// shapes, as three lines (z line, y line, x line; the centre sits in the z line).
+constexpr int kGenericBytes = 3584;
+
+template <typename T>
+struct GenericArgs {
+    const T* in;
+    T* out;
+    int W, H, D;
+    int M, N, K;       // box extents (x, y, z)
+    int ax, ay, az;    // anchor
+    int boundary;
+    int star;          // 1: coefficients are the three axis lines
+    int skip_zero;     // 1: an exactly-zero coefficient is not a tap
+    T w[kGenericBytes / sizeof(T)];
+};
+
+template <typename T>
+__device__ __forceinline__ T fetch(const GenericArgs<T>& a, int x, int y, int z)
+{
+    if (a.boundary == kClamp) {
+        x = min(max(x, 0), a.W - 1);
+        y = min(max(y, 0), a.H - 1);
+        z = min(max(z, 0), a.D - 1);
+    } else if (x < 0 || x >= a.W || y < 0 || y >= a.H || z < 0 || z >= a.D) {
+        return T(0);
+    }
+    return a.in[((size_t)z * a.H + y) * a.W + x];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void generic_kernel(const GenericArgs<T> a)
+{
+    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int z = blockIdx.z;
+    if (x >= a.W || y >= a.H) return;
+    T sum = T(0);
+    if (a.star) {
+        for (int k = 0; k < a.K; ++k) {
+            const T c = a.w[k];
+            if (a.skip_zero && c == T(0)) continue;
+            sum = fma_t(c, fetch(a, x, y, z + k - a.az), sum);
+        }
+        for (int n = 0; n < a.N; ++n) {
+            const T c = a.w[a.K + n];
+            if (n == a.ay || (a.skip_zero && c == T(0))) continue;
+            sum = fma_t(c, fetch(a, x, y + n - a.ay, z), sum);
+        }
+        for (int m = 0; m < a.M; ++m) {
+            const T c = a.w[a.K + a.N + m];
+            if (m == a.ax || (a.skip_zero && c == T(0))) continue;
+            sum = fma_t(c, fetch(a, x + m - a.ax, y, z), sum);
+        }
+    } else {
+        for (int k = 0; k < a.K; ++k)
+            for (int n = 0; n < a.N; ++n)
+                for (int m = 0; m < a.M; ++m) {
+                    const T c = a.w[(k * a.N + n) * a.M + m];
+                    if (a.skip_zero && c == T(0)) continue;
+                    sum = fma_t(c, fetch(a, x + m - a.ax, y + n - a.ay, z + k - a.az), sum);
+                }
+    }
+    a.out[((size_t)z * a.H + y) * a.W + x] = sum;
+}
+
+template <typename T>
+bool is_star(const T* c, int M, int N, int K, int ax, int ay, int az)
+{
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            for (int m = 0; m < M; ++m)
+                if (c[(k * N + n) * M + m] != T(0) && ((k != az) + (n != ay) + (m != ax)) > 1) return false;
+    return true;
+}
+
+// Largest number of simultaneously non-zero offset components among the taps (0..3).
+template <typename T>
+int tap_budget(const T* c, int M, int N, int K, int ax, int ay, int az)
+{
+    int b = 0;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            for (int m = 0; m < M; ++m)
+                if (c[(k * N + n) * M + m] != T(0)) {
+                    const int u = (k != az) + (n != ay) + (m != ax);
+                    if (u > b) b = u;
+                }
+    return b;
+}
+
+template <typename T>
+bool generic_fits(const T* c, int M, int N, int K, int ax, int ay, int az, bool allow_star)
+{
+    const size_t cap = kGenericBytes / sizeof(T);
+    if ((size_t)M * N * K <= cap) return true;
+    return allow_star && is_star(c, M, N, K, ax, ay, az) && (size_t)(M + N + K) <= cap;
+}
+
+template <typename T>
+hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, int M, int N, int K, int ax,
+                          int ay, int az, int boundary, bool skip_zero, hipStream_t stream)
+{
+    GenericArgs<T> a;
+    a.in = in;
+    a.out = out;
+    a.W = W; a.H = H; a.D = D;
+    a.M = M; a.N = N; a.K = K;
+    a.ax = ax; a.ay = ay; a.az = az;
+    a.boundary = boundary;
+    a.skip_zero = skip_zero ? 1 : 0;
+    const size_t cap = kGenericBytes / sizeof(T);
+    if ((size_t)M * N * K <= cap) {
+        a.star = 0;
+        for (int i = 0; i < M * N * K; ++i) a.w[i] = c[i];
+    } else {
+        a.star = 1;
+        for (int k = 0; k < K; ++k) a.w[k] = c[(k * N + ay) * M + ax];
+        for (int n = 0; n < N; ++n) a.w[K + n] = c[(az * N + n) * M + ax];
+        for (int m = 0; m < M; ++m) a.w[K + N + m] = c[(az * N + ay) * M + m];
+    }
+    if (ceil_div(H, 4) > 65535 || D > 65535) return hipErrorInvalidValue;
+    dim3 grid(ceil_div(W, 64), ceil_div(H, 4), D);
+    hipLaunchKernelGGL(generic_kernel<T>, grid, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// ---- validation helpers ------------------------------------------------------------------
+int check_enums(int boundary, int dtype)
+{
+    if (boundary != SSAM_BOUNDARY_ZERO && boundary != SSAM_BOUNDARY_CLAMP) return SSAM_ERR_ENUM;
+    if (dtype != SSAM_F32 && dtype != SSAM_F64) return SSAM_ERR_ENUM;
+    return SSAM_OK;
+}
+
+int check_dims(int W, int H, int D)
+{
+    if (W <= 0 || H <= 0 || D <= 0) return SSAM_ERR_DIM;
+    if ((long long)W * H * D > 2147483647LL) return SSAM_ERR_DIM;
+    return SSAM_OK;
+}
+
+bool overlap(const void* a, const void* b, size_t bytes)
+{
+    const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + bytes && pb < pa + bytes;
+}
+
+size_t elem(int dtype) { return dtype == SSAM_F32 ? 4 : 8; }
+
+// ---- dispatch ---------------------------------------------------------------------------
+struct Choice2D {
+    const Instance2D* inst = nullptr;
+};
+
+template <typename T>
+const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics)
+{
+    const T* w = static_cast<const T*>(p.w);
+    int budget = 2;
+    if (stencil_semantics) {
+        budget = tap_budget<T>(w, p.M, p.N, 1, p.ax, p.ay, 0);
+        if (budget == 0) budget = 1;
+    }
+    const Instance2D* best = nullptr;
+    for (const Instance2D& i : registry2d()) {
+        if (i.dtype != p.dtype || i.M != p.M || i.N != p.N || i.AX != p.ax) continue;
+        if (i.budget < budget) continue;
+        if (i.budget == 1 && p.ay != p.N / 2) continue;   // star instances assume the centre row
+        if (!best || i.budget < best->budget) best = &i;
+    }
+    return best;
+}
+
+int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, std::string* name)
+{
+    const Tuning tu = current_tuning();
+    const Instance2D* inst = nullptr;
+    if (tu.force_generic <= 0)
+        inst = p.dtype == SSAM_F32 ? pick2d<float>(p, stencil_semantics) : pick2d<double>(p, stencil_semantics);
+    if (inst) {
+        if (name) *name = inst->name;
+        return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    }
+    if (name) *name = "generic_direct";
+    if (geo) {
+        *geo = Geometry();
+        geo->blocks = ceil_div(p.W, 64) * ceil_div(p.H, 4);
+    }
+    bool fits = p.dtype == SSAM_F32
+                    ? generic_fits<float>((const float*)p.w, p.M, p.N, 1, p.ax, p.ay, 0, stencil_semantics)
+                    : generic_fits<double>((const double*)p.w, p.M, p.N, 1, p.ax, p.ay, 0, stencil_semantics);
+    if (!fits) return SSAM_ERR_SHAPE;
+    if (dry) return SSAM_OK;
+    hipError_t e = p.dtype == SSAM_F32
+                       ? launch_generic<float>((const float*)p.in, (float*)p.out, p.W, p.H, 1, (const float*)p.w, p.M,
+                                               p.N, 1, p.ax, p.ay, 0, p.boundary, stencil_semantics, p.stream)
+                       : launch_generic<double>((const double*)p.in, (double*)p.out, p.W, p.H, 1, (const double*)p.w,
+                                                p.M, p.N, 1, p.ax, p.ay, 0, p.boundary, stencil_semantics, p.stream);
+    return e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+}
+
+template <typename T>
+const Instance3D* pick3d(const Problem3D& p)
+{
+    const T* c = static_cast<const T*>(p.c);
+    int budget = tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
+    if (budget == 0) budget = 1;
+    const Instance3D* best = nullptr;
+    for (const Instance3D& i : registry3d()) {
+        if (i.dtype != p.dtype || i.rx != p.rx || i.ry != p.ry || i.rz != p.rz || i.budget < budget) continue;
+        if (!best || i.budget < best->budget) best = &i;
+    }
+    return best;
+}
+
+int run3d(const Problem3D& p, Geometry* geo, bool dry, std::string* name)
+{
+    const Tuning tu = current_tuning();
+    if (p.D == 1 && p.rz == 0) {   // a 2D problem through the 3D door
+        Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
+        return run2d(q, true, geo, dry, name);
+    }
+    const Instance3D* inst = nullptr;
+    if (tu.force_generic <= 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p) : pick3d<double>(p);
+    if (inst) {
+        if (name) *name = inst->name;
+        return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    }
+    if (name) *name = "generic_direct";
+    if (geo) {
+        *geo = Geometry();
+        geo->blocks = ceil_div(p.W, 64) * ceil_div(p.H, 4) * p.D;
+    }
+    const int M = 2 * p.rx + 1, N = 2 * p.ry + 1, K = 2 * p.rz + 1;
+    bool fits = p.dtype == SSAM_F32 ? generic_fits<float>((const float*)p.c, M, N, K, p.rx, p.ry, p.rz, true)
+                                    : generic_fits<double>((const double*)p.c, M, N, K, p.rx, p.ry, p.rz, true);
+    if (!fits) return SSAM_ERR_SHAPE;
+    if (dry) return SSAM_OK;
+    hipError_t e = p.dtype == SSAM_F32
+                       ? launch_generic<float>((const float*)p.in, (float*)p.out, p.W, p.H, p.D, (const float*)p.c, M,
+                                               N, K, p.rx, p.ry, p.rz, p.boundary, true, p.stream)
+                       : launch_generic<double>((const double*)p.in, (double*)p.out, p.W, p.H, p.D,
+                                                (const double*)p.c, M, N, K, p.rx, p.ry, p.rz, p.boundary, true,
+                                                p.stream);
+    return e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+}
+
+int validate_conv(const void* in, const void* out, int W, int H, const void* f, int M, int N, int* ax, int* ay,
+                  int boundary, int dtype)
+{
+    if (!in || !out || !f) return SSAM_ERR_NULL;
+    if (int e = check_enums(boundary, dtype)) return e;
+    if (int e = check_dims(W, H, 1)) return e;
+    if (M <= 0 || N <= 0 || M > SSAM_MAX_FILTER || N > SSAM_MAX_FILTER) return SSAM_ERR_SHAPE;
+    if (*ax == -1) *ax = M / 2;
+    if (*ay == -1) *ay = N / 2;
+    if (*ax < 0 || *ax >= M || *ay < 0 || *ay >= N) return SSAM_ERR_SHAPE;
+    if (overlap(in, out, (size_t)W * H * elem(dtype))) return SSAM_ERR_ALIAS;
+    return SSAM_OK;
+}
+
+int validate_stencil(const void* in, const void* out, int W, int H, int D, const void* c, int rx, int ry, int rz,
+                     int boundary, int dtype)
+{
+    if (!in || !out || !c) return SSAM_ERR_NULL;
+    if (int e = check_enums(boundary, dtype)) return e;
+    if (int e = check_dims(W, H, D)) return e;
+    if (rx < 0 || ry < 0 || rz < 0 || rx > SSAM_MAX_RADIUS || ry > SSAM_MAX_RADIUS || rz > SSAM_MAX_RADIUS)
+        return SSAM_ERR_SHAPE;
+    if (overlap(in, out, (size_t)W * H * D * elem(dtype))) return SSAM_ERR_ALIAS;
+    return SSAM_OK;
+}
+
+int describe(int rc, const std::string& name, const Geometry& g, char* buf, int buflen)
+{
+    if (buf && buflen > 0) {
+        snprintf(buf, (size_t)buflen,
+                 "%s V=%d P=%d halo_lanes=%d+%d valid_lanes=%d strips_x=%d tiles_y=%d tiles_z=%d rows_per_wave=%d "
+                 "planes_per_wave=%d tiles=%ld blocks=%d xcd_remap=%d",
+                 name.c_str(), g.V, g.P, g.halo_left, g.halo_right, g.valid_lanes, g.strips_x, g.tiles_y, g.tiles_z,
+                 g.rows_per_wave, g.planes_per_wave, g.tiles, g.blocks, g.xcd_remap);
+    }
+    return rc;
+}
+
+}  // namespace
+}  // namespace ssam
+
+using namespace ssam;
+
+extern "C" {
+
+int ssam_conv2d(const void* d_in, void* d_out, int W, int H, const void* h_filter, int M, int N, int ax, int ay,
+                int boundary, int dtype, void* hip_stream)
+{
+    if (int e = validate_conv(d_in, d_out, W, H, h_filter, M, N, &ax, &ay, boundary, dtype)) return e;
+    Problem2D p{d_in, d_out, W, H, h_filter, M, N, ax, ay, boundary, dtype, (hipStream_t)hip_stream};
+    return run2d(p, false, nullptr, false, nullptr);
+}
+
+int ssam_stencil2d(const void* d_in, void* d_out, int W, int H, const void* h_coef, int rx, int ry, int boundary,
+                   int dtype, void* hip_stream)
+{
+    if (int e = validate_stencil(d_in, d_out, W, H, 1, h_coef, rx, ry, 0, boundary, dtype)) return e;
+    Problem2D p{d_in, d_out, W, H, h_coef, 2 * rx + 1, 2 * ry + 1, rx, ry, boundary, dtype, (hipStream_t)hip_stream};
+    return run2d(p, true, nullptr, false, nullptr);
+}
+
+int ssam_stencil3d(const void* d_in, void* d_out, int W, int H, int D, const void* h_coef, int rx, int ry, int rz,
+                   int boundary, int dtype, void* hip_stream)
+{
+    if (int e = validate_stencil(d_in, d_out, W, H, D, h_coef, rx, ry, rz, boundary, dtype)) return e;
+    Problem3D p{d_in, d_out, W, H, D, h_coef, rx, ry, rz, boundary, dtype, (hipStream_t)hip_stream};
+    return run3d(p, nullptr, false, nullptr);
+}
+
+int ssam_stencil_iterate(void* d_a, void* d_b, int W, int H, int D, const void* h_coef, int rx, int ry, int rz,
+                         int boundary, int dtype, int steps, void* hip_stream, void** d_result)
+{
+    if (int e = validate_stencil(d_a, d_b, W, H, D, h_coef, rx, ry, rz, boundary, dtype)) return e;
+    if (steps < 0) return SSAM_ERR_SHAPE;
+    void* src = d_a;
+    void* dst = d_b;
+    for (int t = 0; t < steps; ++t) {
+        Problem3D p{src, dst, W, H, D, h_coef, rx, ry, rz, boundary, dtype, (hipStream_t)hip_stream};
+        if (int e = run3d(p, nullptr, false, nullptr)) return e;
+        void* tmp = src;
+        src = dst;
+        dst = tmp;
+    }
+    if (d_result) *d_result = src;
+    return SSAM_OK;
+}
+
+const char* ssam_status_string(int status)
+{
+    switch (status) {
+        case SSAM_OK: return "ok";
+        case SSAM_ERR_NULL: return "null pointer argument";
+        case SSAM_ERR_DIM: return "grid dimension not positive or grid too large";
+        case SSAM_ERR_SHAPE: return "filter, radius, anchor or step count out of range";
+        case SSAM_ERR_ENUM: return "unknown dtype, boundary or tuning name";
+        case SSAM_ERR_ALIAS: return "input and output buffers overlap";
+        case SSAM_ERR_HIP: return "HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+int ssam_set_tuning(const char* name, int value)
+{
+    if (!name) return SSAM_ERR_NULL;
+    if (!strcmp(name, "rows_per_wave")) g_rows_per_wave = value;
+    else if (!strcmp(name, "valid_lanes")) g_valid_lanes = value;
+    else if (!strcmp(name, "planes_per_wave")) g_planes_per_wave = value;
+    else if (!strcmp(name, "xcd_remap")) g_xcd_remap = value;
+    else if (!strcmp(name, "force_generic")) g_force_generic = value;
+    else return SSAM_ERR_ENUM;
+    return SSAM_OK;
+}
+
+int ssam_describe(int kind, int W, int H, int D, const void* h_coef, int a, int b, int c, int boundary, int dtype,
+                  char* buf, int buflen)
+{
+    void* out = nullptr;   // describe plans only: no pointer is dereferenced, no kernel runs
+    std::string name;
+    Geometry g;
+    if (kind == 0) {
+        int ax = -1, ay = -1;
+        if (!h_coef) return SSAM_ERR_NULL;
+        if (int e = check_enums(boundary, dtype)) return e;
+        if (int e = check_dims(W, H, 1)) return e;
+        if (a <= 0 || b <= 0 || a > SSAM_MAX_FILTER || b > SSAM_MAX_FILTER) return SSAM_ERR_SHAPE;
+        ax = a / 2;
+        ay = b / 2;
+        Problem2D p{nullptr, out, W, H, h_coef, a, b, ax, ay, boundary, dtype, nullptr};
+        return describe(run2d(p, false, &g, true, &name), name, g, buf, buflen);
+    }
+    if (kind == 1 || kind == 2) {
+        if (!h_coef) return SSAM_ERR_NULL;
+        if (int e = check_enums(boundary, dtype)) return e;
+        if (kind == 1) { D = 1; c = 0; }
+        if (int e = check_dims(W, H, D)) return e;
+        if (a < 0 || b < 0 || c < 0 || a > SSAM_MAX_RADIUS || b > SSAM_MAX_RADIUS || c > SSAM_MAX_RADIUS)
+            return SSAM_ERR_SHAPE;
+        Problem3D p{nullptr, out, W, H, D, h_coef, a, b, c, boundary, dtype, nullptr};
+        return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
+    }
+    return SSAM_ERR_ENUM;
+}
+
+}  // extern "C"

@@ -1,0 +1,252 @@
+// Device-side building blocks shared by the 2D and 3D kernels (gfx950, wave64).
+//
+// The paper's execution model (Sec. 3.3): (i) a register cache per lane, (ii) partial sums
+// handed to the neighbouring lane, (iii) all lanes accumulating in parallel.  On CDNA4 the
+// hand-over is a DPP whole-wave shift by one lane (no LDS traffic, no bpermute), and one
+// lane owns V adjacent columns, loaded as one 16-byte vector, so that one shift moves the
+// partial sums of V outputs and only ceil(reach/V) shifts are needed per filter side
+// (Sec. 5.4: keep horizontal transfers few).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
+
+namespace ssam {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kXcds = 8;
+
+enum : int { kZero = 0, kClamp = 1 };
+
+// ---- whole-wave shift by one lane ------------------------------------------------------
+// shift_up:   lane L receives the value lane L-1 held (lane 0 receives 0).
+// shift_down: lane L receives the value lane L+1 held (lane 63 receives 0).
+// DPP control 0x138 = wave_shr:1, 0x130 = wave_shl:1 (GFX9 encoding).
+__device__ __forceinline__ int dpp_up(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, false); }
+__device__ __forceinline__ int dpp_down(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x130, 0xf, 0xf, false); }
+
+__device__ __forceinline__ float shift_up(float v) { return __builtin_bit_cast(float, dpp_up(__builtin_bit_cast(int, v))); }
+__device__ __forceinline__ float shift_down(float v) { return __builtin_bit_cast(float, dpp_down(__builtin_bit_cast(int, v))); }
+
+struct Halves { int lo, hi; };
+__device__ __forceinline__ double shift_up(double v)
+{
+    Halves h = __builtin_bit_cast(Halves, v);
+    h.lo = dpp_up(h.lo);
+    h.hi = dpp_up(h.hi);
+    return __builtin_bit_cast(double, h);
+}
+__device__ __forceinline__ double shift_down(double v)
+{
+    Halves h = __builtin_bit_cast(Halves, v);
+    h.lo = dpp_down(h.lo);
+    h.hi = dpp_down(h.hi);
+    return __builtin_bit_cast(double, h);
+}
+
+__device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// ---- V-wide vector access --------------------------------------------------------------
+template <typename T, int V> struct VecOf;
+template <> struct VecOf<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct VecOf<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct VecOf<float, 1> { typedef float type; };
+template <> struct VecOf<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
+template <> struct VecOf<double, 1> { typedef double type; };
+
+template <typename T, int V>
+__device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V])
+{
+    if constexpr (V == 1) {
+        dst[0] = *p;
+    } else {
+        typedef typename VecOf<T, V>::type vec_t;
+        const vec_t v = *reinterpret_cast<const vec_t*>(p);
+#pragma unroll
+        for (int i = 0; i < V; ++i) dst[i] = v[i];
+    }
+}
+
+template <typename T, int V>
+__device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V])
+{
+    if constexpr (V == 1) {
+        *p = src[0];
+    } else {
+        typedef typename VecOf<T, V>::type vec_t;
+        vec_t v;
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = src[i];
+        *reinterpret_cast<vec_t*>(p) = v;
+    }
+}
+
+// ---- tap masks ------------------------------------------------------------------------
+// Coefficients are run-time data; only the *shape* is compiled in, as in the paper's
+// one-instance-per-(M,N) template.  A mask describes one filter slice of width M (x) and
+// height N (y) anchored at (AX, AY): which (n, m) are taps, how far they reach sideways,
+// and where each tap's coefficient sits in the packed array the kernel receives.
+//
+// BUDGET is how many offset components may be non-zero at once: for a 2D slice 2 = dense
+// box, 1 = star (taps on the axes only), 0 = the anchor alone.
+template <int M, int N, int AX, int AY, int BUDGET>
+struct TapMask {
+    static constexpr int kM = M, kN = N, kAX = AX, kAY = AY;
+    static __host__ __device__ constexpr bool tap(int n, int m) { return (n != AY ? 1 : 0) + (m != AX ? 1 : 0) <= BUDGET; }
+    static constexpr int kLeft = BUDGET >= 1 ? AX : 0;            // farthest tap left of the anchor
+    static constexpr int kRight = BUDGET >= 1 ? M - 1 - AX : 0;   // farthest tap right of the anchor
+    // packed coefficients: dense [n][m] for a box; for a star the N column values then the M row values
+    static constexpr int kNW = BUDGET >= 2 ? M * N : (BUDGET == 1 ? M + N : 1);
+    static __host__ __device__ constexpr int widx(int n, int m)
+    {
+        return BUDGET >= 2 ? n * M + m : (BUDGET == 1 ? (n != AY ? n : N + m) : 0);
+    }
+};
+
+// Slice dz of a 3D stencil of radii (RX, RY, RZ); BUDGET = 1 star, 2 faces+edges, 3 dense box.
+template <int RX, int RY, int RZ, int BUDGET, int DZ>
+struct SliceMask {
+    static constexpr int kM = 2 * RX + 1, kN = 2 * RY + 1, kAX = RX, kAY = RY;
+    static constexpr int kUsed = DZ != 0 ? 1 : 0;
+    static __host__ __device__ constexpr bool tap(int n, int m) { return kUsed + (n != RY ? 1 : 0) + (m != RX ? 1 : 0) <= BUDGET; }
+    static constexpr int kLeft = BUDGET - kUsed >= 1 ? RX : 0;
+    static constexpr int kRight = kLeft;
+    // packed coefficients: dense [dz][dy][dx] unless star, which stores the z line, the y line, the x line
+    static constexpr int kNW = BUDGET == 1 ? (2 * RZ + 1) + (2 * RY + 1) + (2 * RX + 1)
+                                           : (2 * RZ + 1) * (2 * RY + 1) * (2 * RX + 1);
+    static __host__ __device__ constexpr int widx(int n, int m)
+    {
+        return BUDGET == 1 ? (DZ != 0 ? DZ + RZ
+                                      : (n != RY ? (2 * RZ + 1) + n : (m != RX ? (2 * RZ + 1) + (2 * RY + 1) + m : RZ)))
+                           : ((DZ + RZ) * kN + n) * kM + m;
+    }
+};
+
+// ---- the systolic row evaluation --------------------------------------------------------
+// For P window positions p (the sliding window of Sec. 4.2) computes
+//     acc[p][j] (+)= sum over taps (n, m) of  w[n*M + m] * column(x_j + m - AX)[p + n]
+// where lane L's register cache r[k][i] holds row k of its own column L*V + i, and x_j is
+// the lane's own column j: the result lands in the lane that owns the output column, so
+// loads and stores are both V-aligned.
+//
+// Dependency graph (the paper's D): two chains of partial sums converge on the owning lane.
+// Taps left of the anchor are accumulated by the lanes to the left and travel up-lane
+// (towards higher lane ids); taps right of the anchor travel down-lane.  At distance d from the owner
+// a lane adds the products of its own columns that fall inside the filter footprint
+// (Sec. 4.3: N-term column inner products), then hands the V partial sums on (Sec. 4.4).
+// After ceil(kLeft/V) + ceil(kRight/V) shifts the owner adds the columns it holds itself.
+// Lanes nearer than ceil(kLeft/V) to the low end of the wave, or ceil(kRight/V) to the
+// high end, end with incomplete sums: they are the overlapped-blocking halo (Sec. 4.5).
+template <typename T, int V, int P, class Mask, bool ACCUMULATE, int ROWS>
+__device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], const T* __restrict__ w, T (&acc)[P][V])
+{
+    constexpr int N = Mask::kN, AX = Mask::kAX;
+    static_assert(ROWS >= N + P - 1, "register cache too small for the sliding window");
+    constexpr int DL = (Mask::kLeft + V - 1) / V;
+    constexpr int DR = (Mask::kRight + V - 1) / V;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        T sum[V];
+        bool have = ACCUMULATE;   // folds to a constant after unrolling: does `sum` hold a value yet
+        if constexpr (ACCUMULATE) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[j] = acc[p][j];
+        }
+        // chain arriving from the left (lower lane ids)
+        if constexpr (DL > 0) {
+            T s[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) s[j] = T(0);
+#pragma unroll
+            for (int d = DL; d >= 1; --d) {
+#pragma unroll
+                for (int j = 0; j < V; ++j)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        const int dx = i - j - d * V;       // this column relative to the output column
+                        if (dx >= -Mask::kLeft && dx <= -1) {
+#pragma unroll
+                            for (int n = 0; n < N; ++n)
+                                if (Mask::tap(n, AX + dx)) s[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], s[j]);
+                        }
+                    }
+#pragma unroll
+                for (int j = 0; j < V; ++j) s[j] = shift_up(s[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[j] = have ? sum[j] + s[j] : s[j];
+            have = true;
+        }
+        // chain arriving from the right (higher lane ids)
+        if constexpr (DR > 0) {
+            T s[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) s[j] = T(0);
+#pragma unroll
+            for (int d = DR; d >= 1; --d) {
+#pragma unroll
+                for (int j = 0; j < V; ++j)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        const int dx = i - j + d * V;
+                        if (dx >= 1 && dx <= Mask::kRight) {
+#pragma unroll
+                            for (int n = 0; n < N; ++n)
+                                if (Mask::tap(n, AX + dx)) s[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], s[j]);
+                        }
+                    }
+#pragma unroll
+                for (int j = 0; j < V; ++j) s[j] = shift_down(s[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[j] = have ? sum[j] + s[j] : s[j];
+            have = true;
+        }
+        if (!have) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[j] = T(0);
+        }
+        // the owner's own columns
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const int dx = i - j;
+                if (dx >= -Mask::kLeft && dx <= Mask::kRight) {
+#pragma unroll
+                    for (int n = 0; n < N; ++n)
+                        if (Mask::tap(n, AX + dx)) sum[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], sum[j]);
+                }
+            }
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[p][j] = sum[j];
+    }
+}
+
+// Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}) in order.
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// Map the hardware block id to a logical one so that consecutive logical blocks (which
+// share halo rows and cache lines) run on the same XCD and hence behind the same L2:
+// hardware deals block b to XCD b % 8.  nblocks_padded is a multiple of 8.
+__device__ __forceinline__ int logical_block(int b, int nblocks_padded, int remap)
+{
+    if (!remap) return b;
+    const int per = nblocks_padded / kXcds;
+    return (b % kXcds) * per + b / kXcds;
+}
+
+}  // namespace ssam

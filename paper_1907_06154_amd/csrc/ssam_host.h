@@ -1,0 +1,119 @@
+// Host-side types shared by the dispatcher (ssam_api.cpp) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "../../include/ssam.h"
+
+#define SSAM_CAT_(a, b) a##b
+#define SSAM_CAT(a, b) SSAM_CAT_(a, b)
+
+namespace ssam {
+
+// Launch parameters a caller may override through ssam_set_tuning (negative = built-in).
+struct Tuning {
+    int rows_per_wave = -1;    // 2D: output rows one wave marches over
+    int valid_lanes = -1;      // lanes of a wave that store results (the rest are halo)
+    int planes_per_wave = -1;  // 3D: output planes one wave marches over
+    int xcd_remap = -1;        // 1: consecutive logical blocks share an XCD
+    int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
+};
+
+struct Problem2D {
+    const void* in;
+    void* out;
+    int W, H;
+    const void* w;  // host, [N][M]
+    int M, N, ax, ay;
+    int boundary, dtype;
+    hipStream_t stream;
+};
+
+struct Problem3D {
+    const void* in;
+    void* out;
+    int W, H, D;
+    const void* c;  // host, [2rz+1][2ry+1][2rx+1]
+    int rx, ry, rz;
+    int boundary, dtype;
+    hipStream_t stream;
+};
+
+// Tile geometry of one launch (all host arithmetic; also reported by ssam_describe).
+struct Geometry {
+    int V = 0, P = 0;          // columns per lane, window positions per chunk
+    int halo_left = 0, halo_right = 0;  // halo lanes on each side of a wave
+    int valid_lanes = 0;       // lanes that store
+    int strips_x = 0;          // tiles along x, each valid_lanes*V columns wide
+    int tiles_y = 0;           // tiles along y
+    int tiles_z = 1;           // tiles along z (3D)
+    int rows_per_wave = 0;     // 2D: rows per tile; 3D: P
+    int planes_per_wave = 0;   // 3D
+    long tiles = 0;            // waves with work
+    int blocks = 0;            // launched blocks (padded to a multiple of 8 when remapped)
+    int xcd_remap = 0;
+};
+
+typedef hipError_t (*Launch2DFn)(const Problem2D&, const Tuning&, Geometry*, bool dry_run);
+typedef hipError_t (*Launch3DFn)(const Problem3D&, const Tuning&, Geometry*, bool dry_run);
+
+struct Instance2D {
+    const char* name;
+    int dtype, M, N, AX, budget;  // budget 2 = dense box, 1 = star
+    Launch2DFn launch;
+};
+
+struct Instance3D {
+    const char* name;
+    int dtype, rx, ry, rz, budget;  // budget = max number of non-zero offset components (1 star, 2, 3 box)
+    Launch3DFn launch;
+};
+
+std::vector<Instance2D>& registry2d();
+std::vector<Instance3D>& registry3d();
+
+struct Register2D {
+    explicit Register2D(const Instance2D& i) { registry2d().push_back(i); }
+};
+struct Register3D {
+    explicit Register3D(const Instance3D& i) { registry3d().push_back(i); }
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+inline bool pointers_aligned(const void* a, const void* b, size_t bytes)
+{
+    return ((uintptr_t)a % bytes) == 0 && ((uintptr_t)b % bytes) == 0;
+}
+
+// Overlapped blocking along x (paper Sec. 4.5 / 4.7 re-derived for 64 lanes of V columns):
+// a wave caches 64*V columns and stores valid_lanes*V of them.  Strips are balanced so the
+// last one is not mostly empty.
+inline void plan_strips(int W, int V, int halo_left, int halo_right, int valid_override, Geometry* g)
+{
+    const int vmax = 64 - halo_left - halo_right;
+    int valid = vmax;
+    if (valid_override > 0 && valid_override < vmax) valid = valid_override;
+    int strips = ceil_div(W, valid * V);
+    if (valid_override <= 0) valid = ceil_div(ceil_div(W, strips), V);  // balance
+    if (valid > vmax) valid = vmax;
+    g->V = V;
+    g->halo_left = halo_left;
+    g->halo_right = halo_right;
+    g->valid_lanes = valid;
+    g->strips_x = ceil_div(W, valid * V);
+}
+
+inline void plan_blocks(Geometry* g, int remap_override)
+{
+    g->tiles = (long)g->strips_x * g->tiles_y * g->tiles_z;
+    int blocks = (int)((g->tiles + 3) / 4);
+    g->xcd_remap = remap_override < 0 ? 1 : (remap_override ? 1 : 0);
+    if (g->xcd_remap) blocks = ceil_div(blocks, 8) * 8;
+    g->blocks = blocks;
+}
+
+}  // namespace ssam

@@ -1,0 +1,216 @@
+// 3D stencil kernel: lanes span x (V columns each), the register cache holds a strip of
+// P + 2*RY rows of the current input plane, and the wave marches along z.
+//
+// The paper couples z-neighbours through shared memory between the warps of a block
+// (Sec. 4.9).  Here the z direction is the "vertical" direction of the software systolic
+// array (Fig. 1d: registers of one thread, direct access): every loaded plane contributes
+// to the 2*RZ+1 output planes in flight, whose partial sums stay in the same lane's
+// registers, so no LDS and no barrier is needed.  Within a plane, each dz-slice of the
+// stencil is a 2D filter evaluated by the same converging partial-sum chains as in 2D.
+#pragma once
+#include "ssam_device.h"
+#include "ssam_host.h"
+
+namespace ssam {
+
+template <typename T, int NW>
+struct Args3D {
+    const T* in;
+    T* out;
+    int W, H, D;
+    int boundary;
+    int strips_x, tiles_y;
+    long tiles;
+    int valid_lanes;
+    int planes_per_wave;
+    int blocks;
+    int xcd_remap;
+    int aligned;
+    T w[NW];
+};
+
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int U, int DZI>
+struct PlaneStep {
+    // Adds input plane `r` (step index u within the unrolled group) into the in-flight planes.
+    static __device__ __forceinline__ void run(const T (&r)[P + 2 * RY][V], const T* __restrict__ w,
+                                               T (&acc)[2 * RZ + 1][P][V])
+    {
+        constexpr int NZ = 2 * RZ + 1;
+        constexpr int DZ = DZI - RZ;
+        constexpr int slot = ((U - DZ) % NZ + NZ) % NZ;
+        typedef SliceMask<RX, RY, RZ, BUDGET, DZ> Mask;
+        // dz = -RZ is the first contribution an output plane receives: assign, do not add
+        if constexpr (DZ == -RZ) systolic_rows<T, V, P, Mask, false, P + 2 * RY>(r, w, acc[slot]);
+        else systolic_rows<T, V, P, Mask, true, P + 2 * RY>(r, w, acc[slot]);
+        if constexpr (DZI + 1 < NZ) PlaneStep<T, V, P, RX, RY, RZ, BUDGET, U, DZI + 1>::run(r, w, acc);
+    }
+};
+
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET>
+__global__ __launch_bounds__(kBlock) void ssam3d_kernel(
+    const Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> a)
+{
+    constexpr int NZ = 2 * RZ + 1;
+    constexpr int C = P + 2 * RY;
+    constexpr int HL = (RX + V - 1) / V;
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lb = logical_block(blockIdx.x, a.blocks, a.xcd_remap);
+    const long tile = (long)lb * kWavesPerBlock + wave;
+    if (tile >= a.tiles) return;
+    const int strip = (int)(tile % a.strips_x);
+    const int ytile = (int)((tile / a.strips_x) % a.tiles_y);
+    const int ztile = (int)(tile / ((long)a.strips_x * a.tiles_y));
+
+    const int W = a.W, H = a.H, D = a.D;
+    const int xo0 = strip * a.valid_lanes * V;
+    const int xw0 = xo0 - HL * V;
+    const int xc = xw0 + lane * V;
+    const int y0 = ytile * P;
+    const int z0 = ztile * a.planes_per_wave;
+    const int z1 = min(z0 + a.planes_per_wave, D);
+    const bool vec_ok = a.aligned && (W % V) == 0;
+    const bool fast_x = vec_ok && xw0 >= 0 && xw0 + kWave * V <= W;
+    const bool clamp = a.boundary == kClamp;
+    const T* __restrict__ in = a.in;
+    const size_t plane = (size_t)W * H;
+
+    auto load_plane = [&](int z, T (&dst)[C][V]) __attribute__((always_inline)) {
+        bool zero_plane = false;
+        if (clamp) z = min(max(z, 0), D - 1);
+        else zero_plane = (z < 0 || z >= D);
+#pragma unroll
+        for (int k = 0; k < C; ++k) {
+            int y = y0 - RY + k;
+            bool zero_row = zero_plane;
+            if (clamp) y = min(max(y, 0), H - 1);
+            else zero_row = zero_row || (y < 0 || y >= H);
+            if (zero_row) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) dst[k][i] = T(0);
+                continue;
+            }
+            const T* rowp = in + (size_t)z * plane + (size_t)y * W;
+            if (fast_x) {
+                load_vec<T, V>(rowp + xc, dst[k]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const int x = xc + i;
+                    if (clamp) dst[k][i] = rowp[min(max(x, 0), W - 1)];
+                    else dst[k][i] = (x >= 0 && x < W) ? rowp[x] : T(0);
+                }
+            }
+        }
+    };
+
+    T acc[NZ][P][V];
+#pragma unroll
+    for (int s = 0; s < NZ; ++s)
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[s][p][j] = T(0);
+
+    // Two plane buffers alternate (the next plane is requested before the current one is
+    // used, so its latency hides behind the arithmetic).  The march is unrolled over
+    // lcm(2, NZ) steps so that buffer parity and accumulator slots are compile-time.
+    constexpr int UNR = 2 * NZ;
+    T buf[2][C][V];
+    const int nt = (z1 - z0) + 2 * RZ;    // input planes z0-RZ .. z1-1+RZ
+    load_plane(z0 - RZ, buf[0]);
+    const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
+
+    for (int tb = 0; tb < nt; tb += UNR) {
+        static_for<UNR>([&](auto uc) __attribute__((always_inline)) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int cur = u & 1;
+            constexpr int ubase = u % NZ;
+            const int t = tb + u;
+            if (t < nt) {
+                const int zin = z0 - RZ + t;
+                if (t + 1 < nt) load_plane(zin + 1, buf[cur ^ 1]);
+                PlaneStep<T, V, P, RX, RY, RZ, BUDGET, ubase, 0>::run(buf[cur], a.w, acc);
+
+                // output plane zin - RZ has now received its last contribution
+                const int zo = zin - RZ;
+                constexpr int slot = ((ubase - RZ) % NZ + NZ) % NZ;
+                if (zo >= z0 && lane_stores) {
+#pragma unroll
+                    for (int p = 0; p < P; ++p) {
+                        const int y = y0 + p;
+                        if (y < H) {
+                            T* rowp = a.out + (size_t)zo * plane + (size_t)y * W;
+                            if (vec_ok) {
+                                store_vec<T, V>(rowp + xc, acc[slot][p]);
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < V; ++i)
+                                    if (xc + i < W) rowp[xc + i] = acc[slot][p][i];
+                            }
+                        }
+                    }
+                }
+            }
+        });
+    }
+}
+
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET>
+hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
+{
+    typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
+    constexpr int HL = (RX + V - 1) / V;
+    constexpr int NX = 2 * RX + 1, NY = 2 * RY + 1, NZ = 2 * RZ + 1;
+    Geometry g;
+    plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g);
+    g.P = P;
+    g.rows_per_wave = P;
+    g.tiles_y = ceil_div(pr.H, P);
+    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
+    if (planes > pr.D) planes = pr.D;
+    g.planes_per_wave = planes;
+    g.tiles_z = ceil_div(pr.D, planes);
+    plan_blocks(&g, tu.xcd_remap);
+    if (geo) *geo = g;
+    if (dry_run) return hipSuccess;
+
+    Args3D<T, Mask0::kNW> a;
+    a.in = static_cast<const T*>(pr.in);
+    a.out = static_cast<T*>(pr.out);
+    a.W = pr.W;
+    a.H = pr.H;
+    a.D = pr.D;
+    a.boundary = pr.boundary;
+    a.strips_x = g.strips_x;
+    a.tiles_y = g.tiles_y;
+    a.tiles = g.tiles;
+    a.valid_lanes = g.valid_lanes;
+    a.planes_per_wave = g.planes_per_wave;
+    a.blocks = g.blocks;
+    a.xcd_remap = g.xcd_remap;
+    a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
+    const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
+    for (int i = 0; i < Mask0::kNW; ++i) a.w[i] = T(0);
+    for (int k = 0; k < NZ; ++k)
+        for (int n = 0; n < NY; ++n)
+            for (int m = 0; m < NX; ++m) {
+                const int used = (k != RZ) + (n != RY) + (m != RX);
+                if (used > BUDGET) continue;
+                int idx;
+                if (BUDGET == 1) idx = k != RZ ? k : (n != RY ? NZ + n : (m != RX ? NZ + NY + m : RZ));
+                else idx = (k * NY + n) * NX + m;
+                a.w[idx] = c[(k * NY + n) * NX + m];
+            }
+    hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET>), dim3(g.blocks), dim3(kBlock), 0,
+                       pr.stream, a);
+    return hipGetLastError();
+}
+
+#define SSAM_INSTANCE_3D(T, DT, V, P, RX, RY, RZ, BUDGET)                                            \
+    static ::ssam::Register3D SSAM_CAT(reg3d_, __COUNTER__)(::ssam::Instance3D{                      \
+        #T "_r" #RX #RY #RZ "_b" #BUDGET "_v" #V "p" #P, DT, RX, RY, RZ, BUDGET,                     \
+        &::ssam::launch3d<T, V, P, RX, RY, RZ, BUDGET>})
+
+}  // namespace ssam

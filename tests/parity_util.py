@@ -1,0 +1,38 @@
+"""Helpers shared by the GPU parity tests: error metric and windowed oracle evaluation."""
+from __future__ import annotations
+
+from typing import Sequence, Tuple
+
+import numpy as np
+
+TOL = {np.dtype(np.float32): 1e-5, np.dtype(np.float64): 1e-12}
+
+
+def normalised_error(got: np.ndarray, want: np.ndarray, coef: np.ndarray, in_max: float) -> float:
+    """max |got - want| / (sum|w| * max|in|): the metric the acceptance tolerance is stated in."""
+    scale = float(np.abs(coef.astype(np.float64)).sum()) * float(in_max)
+    if scale == 0.0:
+        scale = 1.0
+    return float(np.max(np.abs(got.astype(np.float64) - want.astype(np.float64)))) / scale
+
+
+def assert_parity(got: np.ndarray, want: np.ndarray, coef: np.ndarray, in_max: float, what: str = "") -> float:
+    assert got.shape == want.shape and got.dtype == want.dtype, (what, got.shape, want.shape, got.dtype, want.dtype)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite GPU output"
+    err = normalised_error(got, want, coef, in_max)
+    tol = TOL[np.dtype(got.dtype)]
+    assert err <= tol, f"{what}: normalised error {err:.3e} > {tol:.0e}"
+    return err
+
+
+def expanded_window(full_shape: Sequence[int], lo: Sequence[int], hi: Sequence[int],
+                    reach_lo: Sequence[int], reach_hi: Sequence[int]) -> Tuple[Tuple[int, ...], Tuple[int, ...]]:
+    """Window [lo, hi) grown by the dependency reach on each side and clipped to the grid.
+
+    Evaluating the oracle on the grown crop, with the true boundary rule at the crop's edges,
+    gives the true values inside [lo, hi): where the crop was clipped its edge *is* the grid's
+    edge, and elsewhere the crop edge lies at least `reach` away, so the wrong values its
+    artificial boundary produces cannot arrive."""
+    elo = tuple(max(0, l - r) for l, r in zip(lo, reach_lo))
+    ehi = tuple(min(n, h + r) for n, h, r in zip(full_shape, hi, reach_hi))
+    return elo, ehi

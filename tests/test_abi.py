@@ -1,0 +1,131 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+public header declares, validates its arguments before any GPU call, and plans tile
+geometry as the design states.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1907_06154_amd as ssam
+from paper_1907_06154_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_A, FAKE_B = 0x10000000, 0x50000000      # never dereferenced: validation fails first
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(ssam.binding.LIB_PATH):
+        from paper_1907_06154_amd import build
+        build.build()
+    return ssam.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssam.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssam_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_symbols()
+    assert {"ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/ssam.h but not exported"
+
+
+def test_status_strings(L):
+    seen = {ssam.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and ssam.status_string(0) == "ok" and ssam.status_string(99) == "unknown status"
+
+
+def conv(L, d_in=FAKE_A, d_out=FAKE_B, W=64, H=64, filt=None, M=3, N=3, ax=-1, ay=-1, boundary=1, dtype=0):
+    f = np.ones((max(N, 1), max(M, 1)), dtype=np.float32) if filt is None else filt
+    fp = None if filt is False else f.ctypes.data
+    return L.ssam_conv2d(d_in, d_out, W, H, fp, M, N, ax, ay, boundary, dtype, None)
+
+
+def test_conv2d_validation(L):
+    assert conv(L, d_in=None) == 1 and conv(L, d_out=None) == 1 and conv(L, filt=False) == 1
+    assert conv(L, W=0) == 2 and conv(L, H=-3) == 2 and conv(L, W=65536, H=65536) == 2
+    assert conv(L, M=0) == 3 and conv(L, N=33) == 3 and conv(L, ax=3) == 3 and conv(L, ay=-2) == 3
+    assert conv(L, boundary=2) == 4 and conv(L, dtype=7) == 4
+    assert conv(L, d_out=FAKE_A) == 5 and conv(L, d_out=FAKE_A + 64 * 64 * 4 - 4) == 5
+    assert conv(L, d_out=FAKE_A + 64 * 64 * 4) != 5
+
+
+def test_stencil_validation(L):
+    c = np.ones(27, dtype=np.float64)
+    cp = c.ctypes.data
+    assert L.ssam_stencil2d(None, FAKE_B, 8, 8, cp, 1, 1, 0, 1, None) == 1
+    assert L.ssam_stencil2d(FAKE_A, FAKE_B, 8, 0, cp, 1, 1, 0, 1, None) == 2
+    assert L.ssam_stencil2d(FAKE_A, FAKE_B, 8, 8, cp, -1, 1, 0, 1, None) == 3
+    assert L.ssam_stencil2d(FAKE_A, FAKE_B, 8, 8, cp, 9, 1, 0, 1, None) == 3
+    assert L.ssam_stencil2d(FAKE_A, FAKE_B, 8, 8, cp, 1, 1, 5, 1, None) == 4
+    assert L.ssam_stencil3d(FAKE_A, FAKE_A, 8, 8, 8, cp, 1, 1, 1, 0, 1, None) == 5
+    assert L.ssam_stencil3d(FAKE_A, FAKE_B, 8, 8, -1, cp, 1, 1, 1, 0, 1, None) == 2
+    assert L.ssam_stencil3d(FAKE_A, FAKE_B, 2048, 2048, 2048, cp, 1, 1, 1, 0, 1, None) == 2
+    res = ctypes.c_void_p(0)
+    assert L.ssam_stencil_iterate(FAKE_A, FAKE_B, 8, 8, 8, cp, 1, 1, 1, 0, 1, -1, None, ctypes.byref(res)) == 3
+    assert L.ssam_stencil_iterate(FAKE_A, FAKE_A + 8, 8, 8, 8, cp, 1, 1, 1, 0, 1, 3, None, ctypes.byref(res)) == 5
+    # zero steps: nothing to launch, the field stays in d_a
+    assert L.ssam_stencil_iterate(FAKE_A, FAKE_B, 8, 8, 8, cp, 1, 1, 1, 0, 1, 0, None, ctypes.byref(res)) == 0
+    assert res.value == FAKE_A
+
+
+def test_tuning_names(L):
+    assert L.ssam_set_tuning(b"rows_per_wave", 16) == 0 and L.ssam_set_tuning(b"rows_per_wave", -1) == 0
+    assert L.ssam_set_tuning(b"no_such_knob", 1) == 4 and L.ssam_set_tuning(None, 1) == 1
+
+
+def parse(desc):
+    name, *kv = desc.split()
+    out = {}
+    for item in kv:
+        k, v = item.split("=")
+        out[k] = sum(int(t) for t in v.split("+")) if k == "halo_lanes" else int(v)
+    return name, out
+
+
+def test_overlapped_blocking_geometry(L):
+    """Tile plan re-derived from Sec. 4.5 / 4.7 for 64 lanes of V columns: a wave caches 64*V
+    columns, stores valid_lanes*V of them (valid_lanes <= 64 - halo lanes), and the strips cover W."""
+    for (M, N) in wl.CONV_SHAPES:
+        f = wl.seeded_filter(M, N, 1, np.float32)
+        name, g = parse(ssam.ssam_describe("conv2d", (8192, 8192), f, "clamp"))
+        assert name.startswith("float_M%dN%d_b2" % (M, N))
+        V = g["V"]
+        hl, hr = -(-(M // 2) // V), -(-(M - 1 - M // 2) // V)
+        assert V == 4 and g["halo_lanes"] == hl + hr
+        assert g["valid_lanes"] <= 64 - hl - hr
+        assert g["strips_x"] * g["valid_lanes"] * V >= 8192 > (g["strips_x"] - 1) * g["valid_lanes"] * V
+        assert g["rows_per_wave"] % g["P"] == 0 and g["tiles_y"] * g["rows_per_wave"] >= 8192
+        assert g["tiles"] == g["strips_x"] * g["tiles_y"] and g["blocks"] * 4 >= g["tiles"]
+        assert g["blocks"] % 8 == 0
+
+
+def test_shape_classification(L):
+    cases = {
+        "c1_2d5pt_f32": "float_M3N3_b1", "c3_2d_box_r1_f64": "double_M3N3_b2", "c3_2d_box_r2_f64": "double_M5N5_b2",
+        "c3_2d_star_r4_f64": "double_M9N9_b1", "c4_3d_star_r1_f64": "double_r111_b1",
+        "c4_3d_box_r1_f64": "double_r111_b3", "c4_3d_faces_edges_f64": "double_r111_b2",
+        "c5_3d_star_r4_f32": "float_r444_b1", "c5_3d_star_r4_f64": "double_r444_b1",
+    }
+    allc = {c.name: c for cs in wl.all_configs().values() for c in cs}
+    for nm, prefix in cases.items():
+        c = allc[nm]
+        coef = c.coef if c.kind == "stencil3d" else c.coef[0]
+        name, g = parse(ssam.ssam_describe(c.kind, c.shape, coef, c.boundary))
+        assert name.startswith(prefix), (nm, name)
+    # a shape without a compiled instance falls to the direct kernel instead of failing
+    name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 7), dtype=np.float32), "zero"))
+    assert name == "generic_direct"
+    # a dense 3D box too large for the argument block is refused
+    with pytest.raises(ssam.SsamError):
+        ssam.ssam_describe("stencil3d", (32, 32, 32), np.ones((9, 9, 9), dtype=np.float64), "zero")
+    # ... but the same radii as a star fit
+    star = np.zeros((17, 17, 17)); star[8, 8, :] = 1; star[8, :, 8] = 1; star[:, 8, 8] = 1
+    name, _ = parse(ssam.ssam_describe("stencil3d", (32, 32, 32), star, "zero"))
+    assert name == "generic_direct"

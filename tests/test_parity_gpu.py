@@ -1,0 +1,216 @@
+"""GPU parity: the HIP path, called through the C ABI (ctypes binding), against the CPU oracle,
+element by element on the same seeded inputs.  Sizes here are small enough for the oracle to
+finish in seconds yet span several wave tiles, ragged tails and the unaligned slow path.
+Tolerance (stated by the acceptance target): max |gpu - oracle| / (sum|w| * max|in|) <= 1e-5
+for fp32, <= 1e-12 for fp64."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_06154_amd import workloads as wl
+from parity_util import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ssam():
+    import paper_1907_06154_amd as s
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    s.lib()   # raises if the HIP library is missing: there is no fallback
+    yield s
+    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic"):
+        s.ssam_set_tuning(name, -1)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+SHAPES_2D = [(70, 300), (37, 259), (5, 7), (1, 1), (64, 1024), (129, 520), (3, 2050)]
+
+
+@pytest.mark.parametrize("MN", wl.CONV_SHAPES + [(2, 2), (4, 6), (7, 7), (1, 5), (5, 1)])
+@pytest.mark.parametrize("boundary", ["clamp", "zero"])
+def test_conv2d_f32(ssam, MN, boundary):
+    M, N = MN
+    filt = wl.seeded_filter(M, N, 300 + 32 * M + N, np.float32)
+    for k, (H, W) in enumerate(SHAPES_2D):
+        img = wl.uniform_field((H, W), 0.0, 1.0, 310 + k, np.float32)
+        print(f"conv2d f32 {M}x{N} {boundary} grid {H}x{W}", flush=True)
+        got = host(ssam.ssam_conv2d(dev(img), filt, boundary))
+        want = oracle.conv2d(img, filt, boundary)
+        assert_parity(got, want, filt, 1.0, f"conv {M}x{N} {boundary} {H}x{W}")
+
+
+@pytest.mark.parametrize("MN", [(3, 3), (5, 5), (9, 9), (4, 3)])
+def test_conv2d_f64_and_anchors(ssam, MN):
+    M, N = MN
+    filt = wl.seeded_filter(M, N, 400 + 32 * M + N, np.float64)
+    img = wl.uniform_field((70, 300), -1.0, 1.0, 401, np.float64)
+    for anchor in (None, (0, 0), (M - 1, N - 1)):
+        for boundary in ("clamp", "zero"):
+            print(f"conv2d f64 {M}x{N} anchor {anchor} {boundary}", flush=True)
+            got = host(ssam.ssam_conv2d(dev(img), filt, boundary, anchor))
+            want = oracle.conv2d(img, filt, boundary, anchor)
+            assert_parity(got, want, filt, 1.0, f"conv f64 {M}x{N} {anchor} {boundary}")
+
+
+STENCILS_2D = [("star", 1), ("star", 2), ("star", 3), ("star", 4), ("box", 1), ("box", 2), ("box", 3), ("box", 4),
+               ("star_wide", 0), ("sparse", 2)]
+
+
+def stencil2d_coef(kind, r, dtype, seed):
+    if kind == "star":
+        mask = wl.mask_star(r, r)
+    elif kind == "box":
+        mask = wl.mask_box(r, r)
+    elif kind == "star_wide":           # different radii per axis: no compiled instance
+        mask = wl.mask_star(5, 2)
+    else:                               # arbitrary zero pattern inside a box
+        mask = wl.mask_box(r, r)
+        mask[0, 0, 1] = mask[0, 2, 3] = mask[0, 4, 4] = False
+    return wl.seeded_coefficients(mask, seed, dtype, -1.0, 1.0, normalise=False)[0]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind,r", STENCILS_2D)
+@pytest.mark.parametrize("boundary", ["zero", "clamp"])
+def test_stencil2d(ssam, dtype, kind, r, boundary):
+    coef = stencil2d_coef(kind, r, dtype, 500 + r)
+    for k, (H, W) in enumerate(SHAPES_2D):
+        fld = wl.uniform_field((H, W), -1.0, 1.0, 510 + k, dtype)
+        print(f"stencil2d {np.dtype(dtype).name} {kind} r{r} {boundary} grid {H}x{W}", flush=True)
+        got = host(ssam.ssam_stencil2d(dev(fld), coef, boundary))
+        want = oracle.stencil(fld, coef, boundary)
+        assert_parity(got, want, coef, 1.0, f"stencil2d {kind} r{r} {boundary} {H}x{W}")
+
+
+SHAPES_3D = [(9, 10, 130), (70, 6, 30), (3, 3, 3), (1, 5, 5), (20, 13, 259), (12, 11, 140), (6, 5, 516)]
+STENCILS_3D = [("star", 1), ("box", 1), ("faces_edges", 1), ("star", 4), ("star", 2), ("box_aniso", 0)]
+
+
+def stencil3d_coef(kind, r, dtype, seed):
+    if kind == "star":
+        mask = wl.mask_star(r, r, r)
+    elif kind == "box":
+        mask = wl.mask_box(r, r, r)
+    elif kind == "faces_edges":
+        mask = wl.mask_faces_edges()
+    else:
+        mask = wl.mask_box(2, 1, 1)     # no compiled instance: direct kernel
+    return wl.seeded_coefficients(mask, seed, dtype, -1.0, 1.0, normalise=False)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind,r", STENCILS_3D)
+@pytest.mark.parametrize("boundary", ["zero", "clamp"])
+def test_stencil3d(ssam, dtype, kind, r, boundary):
+    coef = stencil3d_coef(kind, r, dtype, 600 + r)
+    for k, shape in enumerate(SHAPES_3D):
+        fld = wl.uniform_field(shape, -1.0, 1.0, 610 + k, dtype)
+        print(f"stencil3d {np.dtype(dtype).name} {kind} r{r} {boundary} grid {shape}", flush=True)
+        got = host(ssam.ssam_stencil3d(dev(fld), coef, boundary))
+        want = oracle.stencil(fld, coef, boundary)
+        assert_parity(got, want, coef, 1.0, f"stencil3d {kind} r{r} {boundary} {shape}")
+
+
+@pytest.mark.parametrize("tuning", [
+    {"rows_per_wave": 8}, {"valid_lanes": 17}, {"xcd_remap": 0}, {"planes_per_wave": 5},
+    {"rows_per_wave": 16, "valid_lanes": 40, "planes_per_wave": 3, "xcd_remap": 0}, {"force_generic": 1},
+])
+def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
+    try:
+        for k, v in tuning.items():
+            ssam.ssam_set_tuning(k, v)
+        print(f"tuning {tuning}", flush=True)
+        img = wl.uniform_field((129, 520), 0.0, 1.0, 701, np.float32)
+        filt = wl.seeded_filter(5, 5, 702, np.float32)
+        assert_parity(host(ssam.ssam_conv2d(dev(img), filt, "clamp")), oracle.conv2d(img, filt, "clamp"), filt, 1.0)
+        fld = wl.uniform_field((70, 300), -1.0, 1.0, 703, np.float64)
+        c2 = stencil2d_coef("star", 4, np.float64, 704)
+        assert_parity(host(ssam.ssam_stencil2d(dev(fld), c2, "zero")), oracle.stencil(fld, c2, "zero"), c2, 1.0)
+        f3 = wl.uniform_field((20, 13, 259), -1.0, 1.0, 705, np.float64)
+        for kind, r in (("box", 1), ("star", 4)):
+            c3 = stencil3d_coef(kind, r, np.float64, 706)
+            assert_parity(host(ssam.ssam_stencil3d(dev(f3), c3, "clamp")), oracle.stencil(f3, c3, "clamp"), c3, 1.0)
+    finally:
+        for k in tuning:
+            ssam.ssam_set_tuning(k, -1)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_iterate_matches_oracle_and_ping_pongs(ssam, dtype):
+    cases = [((70, 300), wl.seeded_coefficients(wl.mask_box(2, 2), 801, dtype)[0]),
+             ((70, 300), wl.seeded_coefficients(wl.mask_star(4, 4), 802, dtype)[0]),
+             ((20, 13, 140), wl.seeded_coefficients(wl.mask_star(1, 1, 1), 803, dtype)),
+             ((20, 13, 140), wl.seeded_symmetric_star(4, 3, 804, dtype))]
+    for shape, coef in cases:
+        fld = wl.uniform_field(shape, -1.0, 1.0, 810, dtype)
+        for steps in (0, 1, 2, 7):
+            print(f"iterate {np.dtype(dtype).name} {shape} steps {steps}", flush=True)
+            a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+            res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
+            assert res.data_ptr() == (a if steps % 2 == 0 else b).data_ptr()
+            want = oracle.iterate(fld, coef, steps, "zero")
+            if steps == 0:
+                assert np.array_equal(host(res), fld)
+            else:
+                assert_parity(host(res), want, coef, 1.0, f"iterate {shape} {steps}")
+
+
+def test_results_are_bitwise_reproducible(ssam):
+    img = dev(wl.uniform_field((257, 1031), 0.0, 1.0, 901, np.float32))
+    filt = wl.seeded_filter(9, 9, 902, np.float32)
+    first = host(ssam.ssam_conv2d(img, filt, "clamp"))
+    for _ in range(3):
+        assert np.array_equal(host(ssam.ssam_conv2d(img, filt, "clamp")), first)
+    f3 = dev(wl.uniform_field((40, 21, 300), -1.0, 1.0, 903, np.float64))
+    c3 = stencil3d_coef("star", 4, np.float64, 904)
+    first3 = host(ssam.ssam_stencil3d(f3, c3, "zero"))
+    assert np.array_equal(host(ssam.ssam_stencil3d(f3, c3, "zero")), first3)
+
+
+def test_output_outside_grid_untouched_and_input_preserved(ssam):
+    """The kernels must write exactly W*H elements and never modify the input."""
+    H, W = 37, 259
+    img = wl.uniform_field((H, W), 0.0, 1.0, 911, np.float32)
+    filt = wl.seeded_filter(5, 5, 912, np.float32)
+    big = torch.full((H + 2, W), -7.0, dtype=torch.float32, device="cuda")
+    d_in = dev(img)
+    out_view = big[1:H + 1]
+    ssam.ssam_conv2d(d_in, filt, "clamp", d_out=out_view)
+    res = host(big)
+    assert np.all(res[0] == -7.0) and np.all(res[-1] == -7.0)
+    assert_parity(res[1:H + 1], oracle.conv2d(img, filt, "clamp"), filt, 1.0)
+    assert np.array_equal(host(d_in), img)
+
+
+def test_config1_full(ssam):
+    """Benchmark configuration 1 at its full size: 512x512 fp32 five-point star, zero padding, one sweep."""
+    case = wl.config1()[0]
+    fld = case.field()
+    got = host(ssam.ssam_stencil2d(dev(fld), case.coef[0], case.boundary))
+    want = oracle.stencil(fld, case.coef[0], case.boundary)
+    assert_parity(got, want, case.coef, 1.0, case.name)
+
+
+def test_errors_are_reported_not_launched(ssam):
+    img = dev(np.zeros((8, 8), dtype=np.float32))
+    filt = np.ones((3, 3), dtype=np.float32)
+    with pytest.raises(ssam.SsamError) as e:
+        ssam.ssam_conv2d(img, filt, "clamp", d_out=img)
+    assert e.value.status == 5
+    with pytest.raises(ssam.SsamError) as e:
+        ssam.ssam_conv2d(img, np.ones((40, 3), dtype=np.float32), "clamp")
+    assert e.value.status == 3
+    with pytest.raises(ssam.SsamError) as e:
+        ssam.ssam_stencil_iterate(img, torch.empty_like(img), filt, -1)
+    assert e.value.status == 3
