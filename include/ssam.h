@@ -28,6 +28,8 @@
 #ifndef SSAM_H_
 #define SSAM_H_
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -96,13 +98,21 @@ const char *ssam_status_string(int status);
  * built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 
-/* Describes the kernel instance the dispatcher would pick for a problem, without launching:
- * writes a NUL-terminated description ("conv2d_f32_M3N3_v4p8 grid=... block=...") into buf
- * (at most buflen bytes).  Arguments as for the matching entry point; kind 0 = conv2d,
- * 1 = stencil2d, 2 = stencil3d.  For conv2d pass M,N in rx,ry... see ssam_describe docs in
- * the Python binding.  Runs entirely on the host. */
+/* Planning query, host only (nothing is launched, no pointer is dereferenced except h_coef):
+ * writes a NUL-terminated description of the kernel instance and tile geometry the
+ * dispatcher would use -- e.g. "float_M3N3_b2_v4p8 V=4 P=8 halo_lanes=1+1 valid_lanes=61
+ * strips_x=34 ..." -- into buf (at most buflen bytes).  kind 0 = ssam_conv2d with (a, b) =
+ * (M, N) and the default anchor; kind 1 = ssam_stencil2d with (a, b) = (rx, ry); kind 2 =
+ * ssam_stencil3d with (a, b, c) = (rx, ry, rz).  The tile plan follows the paper's overlapped
+ * blocking (Sec. 4.5, Sec. 4.7) re-derived for 64 lanes of V columns each. */
 int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
                   int boundary, int dtype, char *buf, int buflen);
+
+/* Measurement aid: copies nbytes (a multiple of 16; both pointers 16-byte aligned, not
+ * overlapping) from d_in to d_out with a plain 16-bytes-per-lane kernel on hip_stream.  It is
+ * the bandwidth ceiling for a one-read-one-write kernel and the known-size reference that
+ * hardware traffic counters are scaled by. */
+int ssam_probe_copy(const void *d_in, void *d_out, size_t nbytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

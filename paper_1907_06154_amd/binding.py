@@ -20,7 +20,7 @@ SSAM_F32, SSAM_F64 = 0, 1
 SSAM_BOUNDARY_ZERO, SSAM_BOUNDARY_CLAMP = 0, 1
 BOUNDARY = {"zero": SSAM_BOUNDARY_ZERO, "clamp": SSAM_BOUNDARY_CLAMP}
 EXPORTS = ["ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
-           "ssam_status_string", "ssam_set_tuning", "ssam_describe"]
+           "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy"]
 
 
 class SsamError(RuntimeError):
@@ -48,6 +48,7 @@ def lib() -> ctypes.CDLL:
         L.ssam_status_string.restype = ctypes.c_char_p
         L.ssam_set_tuning.argtypes = [ctypes.c_char_p, ci]
         L.ssam_describe.argtypes = [ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ctypes.c_char_p, ci]
+        L.ssam_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         for name in EXPORTS:
             if name not in ("ssam_status_string",):
                 getattr(L, name).restype = ci
@@ -209,3 +210,14 @@ def ssam_describe(kind: str, shape, coef, boundary: str = "zero") -> str:
         raise ValueError(kind)
     _check(st, "ssam_describe")
     return buf.value.decode()
+
+
+def ssam_probe_copy(d_in, d_out, stream=None):
+    """Plain device copy of d_in into d_out (same size, contiguous): the 1R+1W bandwidth ceiling."""
+    _device_tensor(d_in, "d_in")
+    _device_tensor(d_out, "d_out")
+    nbytes = d_in.numel() * d_in.element_size()
+    if nbytes != d_out.numel() * d_out.element_size():
+        raise ValueError("d_in and d_out must have the same size in bytes")
+    _check(lib().ssam_probe_copy(d_in.data_ptr(), d_out.data_ptr(), nbytes, _stream_ptr(stream)), "ssam_probe_copy")
+    return d_out

@@ -168,6 +168,15 @@ hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, 
     return hipGetLastError();
 }
 
+// ---- plain copy (measurement aid) ---------------------------------------------------------
+// 16 bytes per lane, grid-stride: the bandwidth ceiling a 1-read-1-write kernel can reach, and
+// the known-size reference the hardware traffic counters are scaled by.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) out[i] = in[i];
+}
+
 // ---- validation helpers ------------------------------------------------------------------
 int check_enums(int boundary, int dtype)
 {
@@ -374,6 +383,19 @@ int ssam_stencil_iterate(void* d_a, void* d_b, int W, int H, int D, const void* 
     }
     if (d_result) *d_result = src;
     return SSAM_OK;
+}
+
+int ssam_probe_copy(const void* d_in, void* d_out, size_t nbytes, void* hip_stream)
+{
+    if (!d_in || !d_out) return SSAM_ERR_NULL;
+    if (nbytes == 0 || nbytes % 16 != 0 || ((uintptr_t)d_in % 16) || ((uintptr_t)d_out % 16)) return SSAM_ERR_DIM;
+    if (overlap(d_in, d_out, nbytes)) return SSAM_ERR_ALIAS;
+    const size_t n16 = nbytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                       static_cast<const uint4*>(d_in), static_cast<uint4*>(d_out), n16);
+    return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
 }
 
 const char* ssam_status_string(int status)

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <type_traits>
 #include <utility>
 
@@ -49,6 +50,22 @@ __device__ __forceinline__ double shift_down(double v)
 
 __device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 __device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// ---- coefficients -------------------------------------------------------------------------
+// Coefficients live in the kernel-argument block and are read through a constant-address-space
+// pointer with wave-uniform indices, i.e. by scalar loads into SGPRs: one fetch serves all 64
+// lanes and the multiply-add takes the SGPR as an operand.  This is the CDNA counterpart of
+// the paper's conflict-free broadcast read from shared memory (Sec. 4.6).
+template <typename T>
+using ConstPtr = const T __attribute__((address_space(4)))*;
+
+// Pointer to a member of the kernel's (single, by-value) argument struct at byte offset `off`.
+template <typename T>
+__device__ __forceinline__ ConstPtr<T> kernarg_member(size_t off)
+{
+    typedef const char __attribute__((address_space(4)))* Bytes;
+    return (ConstPtr<T>)((Bytes)__builtin_amdgcn_kernarg_segment_ptr() + off);
+}
 
 // ---- V-wide vector access --------------------------------------------------------------
 template <typename T, int V> struct VecOf;
@@ -99,11 +116,13 @@ struct TapMask {
     static __host__ __device__ constexpr bool tap(int n, int m) { return (n != AY ? 1 : 0) + (m != AX ? 1 : 0) <= BUDGET; }
     static constexpr int kLeft = BUDGET >= 1 ? AX : 0;            // farthest tap left of the anchor
     static constexpr int kRight = BUDGET >= 1 ? M - 1 - AX : 0;   // farthest tap right of the anchor
-    // packed coefficients: dense [n][m] for a box; for a star the N column values then the M row values
+    // packed coefficients: a box is stored column by column ([m][n]) so that the N values one
+    // filter column needs are adjacent and arrive in one wide scalar load; a star stores its N
+    // column values, then its M row values
     static constexpr int kNW = BUDGET >= 2 ? M * N : (BUDGET == 1 ? M + N : 1);
     static __host__ __device__ constexpr int widx(int n, int m)
     {
-        return BUDGET >= 2 ? n * M + m : (BUDGET == 1 ? (n != AY ? n : N + m) : 0);
+        return BUDGET >= 2 ? m * N + n : (BUDGET == 1 ? (n != AY ? n : N + m) : 0);
     }
 };
 
@@ -115,117 +134,17 @@ struct SliceMask {
     static __host__ __device__ constexpr bool tap(int n, int m) { return kUsed + (n != RY ? 1 : 0) + (m != RX ? 1 : 0) <= BUDGET; }
     static constexpr int kLeft = BUDGET - kUsed >= 1 ? RX : 0;
     static constexpr int kRight = kLeft;
-    // packed coefficients: dense [dz][dy][dx] unless star, which stores the z line, the y line, the x line
+    // packed coefficients: dense [dz][dx][dy] (columns adjacent, as in 2D) unless star, which stores
+    // the z line, the y line, the x line
     static constexpr int kNW = BUDGET == 1 ? (2 * RZ + 1) + (2 * RY + 1) + (2 * RX + 1)
                                            : (2 * RZ + 1) * (2 * RY + 1) * (2 * RX + 1);
     static __host__ __device__ constexpr int widx(int n, int m)
     {
         return BUDGET == 1 ? (DZ != 0 ? DZ + RZ
                                       : (n != RY ? (2 * RZ + 1) + n : (m != RX ? (2 * RZ + 1) + (2 * RY + 1) + m : RZ)))
-                           : ((DZ + RZ) * kN + n) * kM + m;
+                           : ((DZ + RZ) * kM + m) * kN + n;
     }
 };
-
-// ---- the systolic row evaluation --------------------------------------------------------
-// For P window positions p (the sliding window of Sec. 4.2) computes
-//     acc[p][j] (+)= sum over taps (n, m) of  w[n*M + m] * column(x_j + m - AX)[p + n]
-// where lane L's register cache r[k][i] holds row k of its own column L*V + i, and x_j is
-// the lane's own column j: the result lands in the lane that owns the output column, so
-// loads and stores are both V-aligned.
-//
-// Dependency graph (the paper's D): two chains of partial sums converge on the owning lane.
-// Taps left of the anchor are accumulated by the lanes to the left and travel up-lane
-// (towards higher lane ids); taps right of the anchor travel down-lane.  At distance d from the owner
-// a lane adds the products of its own columns that fall inside the filter footprint
-// (Sec. 4.3: N-term column inner products), then hands the V partial sums on (Sec. 4.4).
-// After ceil(kLeft/V) + ceil(kRight/V) shifts the owner adds the columns it holds itself.
-// Lanes nearer than ceil(kLeft/V) to the low end of the wave, or ceil(kRight/V) to the
-// high end, end with incomplete sums: they are the overlapped-blocking halo (Sec. 4.5).
-template <typename T, int V, int P, class Mask, bool ACCUMULATE, int ROWS>
-__device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], const T* __restrict__ w, T (&acc)[P][V])
-{
-    constexpr int N = Mask::kN, AX = Mask::kAX;
-    static_assert(ROWS >= N + P - 1, "register cache too small for the sliding window");
-    constexpr int DL = (Mask::kLeft + V - 1) / V;
-    constexpr int DR = (Mask::kRight + V - 1) / V;
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        T sum[V];
-        bool have = ACCUMULATE;   // folds to a constant after unrolling: does `sum` hold a value yet
-        if constexpr (ACCUMULATE) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[j] = acc[p][j];
-        }
-        // chain arriving from the left (lower lane ids)
-        if constexpr (DL > 0) {
-            T s[V];
-#pragma unroll
-            for (int j = 0; j < V; ++j) s[j] = T(0);
-#pragma unroll
-            for (int d = DL; d >= 1; --d) {
-#pragma unroll
-                for (int j = 0; j < V; ++j)
-#pragma unroll
-                    for (int i = 0; i < V; ++i) {
-                        const int dx = i - j - d * V;       // this column relative to the output column
-                        if (dx >= -Mask::kLeft && dx <= -1) {
-#pragma unroll
-                            for (int n = 0; n < N; ++n)
-                                if (Mask::tap(n, AX + dx)) s[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], s[j]);
-                        }
-                    }
-#pragma unroll
-                for (int j = 0; j < V; ++j) s[j] = shift_up(s[j]);
-            }
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[j] = have ? sum[j] + s[j] : s[j];
-            have = true;
-        }
-        // chain arriving from the right (higher lane ids)
-        if constexpr (DR > 0) {
-            T s[V];
-#pragma unroll
-            for (int j = 0; j < V; ++j) s[j] = T(0);
-#pragma unroll
-            for (int d = DR; d >= 1; --d) {
-#pragma unroll
-                for (int j = 0; j < V; ++j)
-#pragma unroll
-                    for (int i = 0; i < V; ++i) {
-                        const int dx = i - j + d * V;
-                        if (dx >= 1 && dx <= Mask::kRight) {
-#pragma unroll
-                            for (int n = 0; n < N; ++n)
-                                if (Mask::tap(n, AX + dx)) s[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], s[j]);
-                        }
-                    }
-#pragma unroll
-                for (int j = 0; j < V; ++j) s[j] = shift_down(s[j]);
-            }
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[j] = have ? sum[j] + s[j] : s[j];
-            have = true;
-        }
-        if (!have) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[j] = T(0);
-        }
-        // the owner's own columns
-#pragma unroll
-        for (int j = 0; j < V; ++j)
-#pragma unroll
-            for (int i = 0; i < V; ++i) {
-                const int dx = i - j;
-                if (dx >= -Mask::kLeft && dx <= Mask::kRight) {
-#pragma unroll
-                    for (int n = 0; n < N; ++n)
-                        if (Mask::tap(n, AX + dx)) sum[j] = fma_t(r[p + n][i], w[Mask::widx(n, AX + dx)], sum[j]);
-                }
-            }
-#pragma unroll
-        for (int j = 0; j < V; ++j) acc[p][j] = sum[j];
-    }
-}
 
 // Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}) in order.
 template <class F, int... Is>
@@ -237,6 +156,146 @@ template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f)
 {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// ---- the systolic row evaluation --------------------------------------------------------
+// A wave-uniform zero the compiler cannot see through.  Added to a coefficient index it pins
+// the scalar load of that coefficient to the place where it is used: without it the
+// compiler hoists every coefficient of a large filter out of the row loop and spills the
+// scalar registers it needs for them.
+__device__ __forceinline__ int opaque_zero()
+{
+    int z;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+    return z;
+}
+
+// Products of one filter column, for all P window positions: the lane's own column i = j + COL
+// multiplies filter column AX + DX and accumulates into the partial sum of output column j.
+// (Sec. 4.3: an N-term inner product between a register vector and a filter column.)
+template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, int ROWS>
+__device__ __forceinline__ void column_products(const T (&r)[ROWS][V], ConstPtr<T> w, T (&s)[P][V])
+{
+    constexpr int N = Mask::kN, AX = Mask::kAX;
+    const int z = PIN ? opaque_zero() : 0;
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        if (Mask::tap(n, AX + DX)) {
+            const T wv = w[Mask::widx(n, AX + DX) + z];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const int i = j + COL;
+                if (i >= 0 && i < V) {
+#pragma unroll
+                    for (int p = 0; p < P; ++p) s[p][j] = fma_t(r[p + n][i], wv, s[p][j]);
+                }
+            }
+        }
+    }
+}
+
+// For P window positions p (the sliding window of Sec. 4.2) computes
+//     out[p][j] = (ACCUMULATE ? in[p][j] : 0) + sum over taps (n, m) of
+//                 w[widx(n, m)] * column(x_j + m - AX)[p + n]
+// where lane L's register cache r[k][i] holds row k of its own column L*V + i, and x_j is
+// the lane's own column j: the result lands in the lane that owns the output column, so
+// loads and stores are both V-aligned.  `in` and `out` may be different arrays (the 3D march
+// uses that to rotate its in-flight planes for free) or the same one.
+//
+// Dependency graph (the paper's D): two chains of partial sums converge on the owning lane.
+// Taps left of the anchor are accumulated by the lanes to the left and travel up-lane
+// (towards higher lane ids); taps right of the anchor travel down-lane.  At distance d from
+// the owner a lane adds the products of its own columns that fall inside the filter
+// footprint, then hands the V partial sums on (Sec. 4.4).  After ceil(kLeft/V) +
+// ceil(kRight/V) shifts the owner adds the columns it holds itself.  Lanes nearer than
+// ceil(kLeft/V) to the low end of the wave, or ceil(kRight/V) to the high end, end with
+// incomplete sums: they are the overlapped-blocking halo (Sec. 4.5).
+template <typename T, int V, int P, class Mask, bool ACCUMULATE, int ROWS>
+__device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], ConstPtr<T> w,
+                                              const T (&in)[P][V], T (&out)[P][V])
+{
+    constexpr int N = Mask::kN;
+    static_assert(ROWS >= N + P - 1, "register cache too small for the sliding window");
+    constexpr int DL = (Mask::kLeft + V - 1) / V;
+    constexpr int DR = (Mask::kRight + V - 1) / V;
+    constexpr bool PIN = Mask::kNW > 64;   // small coefficient sets stay resident in scalar registers
+
+    T sum[P][V];
+    bool have = ACCUMULATE;   // folds to a constant: does `sum` hold a value yet
+    if constexpr (ACCUMULATE) {
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[p][j] = in[p][j];
+    }
+
+    // chain arriving from the left (lower lane ids)
+    if constexpr (DL > 0) {
+        T s[P][V];
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) s[p][j] = T(0);
+        static_for<DL>([&](auto dc) __attribute__((always_inline)) {
+            constexpr int d = DL - decltype(dc)::value;            // DL, DL-1, ..., 1
+            // columns of this lane relative to an output column d lanes up: dx = i - j - d*V
+            static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+                constexpr int dx = decltype(cc)::value - (V - 1) - d * V;
+                if constexpr (dx >= -Mask::kLeft && dx <= -1)
+                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, ROWS>(r, w, s);
+            });
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < V; ++j) s[p][j] = shift_up(s[p][j]);
+        });
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+        have = true;
+    }
+    // chain arriving from the right (higher lane ids)
+    if constexpr (DR > 0) {
+        T s[P][V];
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) s[p][j] = T(0);
+        static_for<DR>([&](auto dc) __attribute__((always_inline)) {
+            constexpr int d = DR - decltype(dc)::value;
+            static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+                constexpr int dx = decltype(cc)::value - (V - 1) + d * V;
+                if constexpr (dx >= 1 && dx <= Mask::kRight)
+                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, ROWS>(r, w, s);
+            });
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < V; ++j) s[p][j] = shift_down(s[p][j]);
+        });
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+        have = true;
+    }
+    if (!have) {
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[p][j] = T(0);
+    }
+    // the owner's own columns: dx = i - j
+    static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+        constexpr int dx = decltype(cc)::value - (V - 1);
+        if constexpr (dx >= -Mask::kLeft && dx <= Mask::kRight)
+            column_products<T, V, P, Mask, dx, dx, PIN, ROWS>(r, w, sum);
+    });
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int j = 0; j < V; ++j) out[p][j] = sum[p][j];
 }
 
 // Map the hardware block id to a logical one so that consecutive logical blocks (which

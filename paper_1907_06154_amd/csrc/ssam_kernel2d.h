@@ -54,6 +54,8 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
     const bool fast_x = vec_ok && xw0 >= 0 && xw0 + kWave * V <= W;   // wave-uniform
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
+    typedef Args2D<T, Mask::kNW> Args;
+    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
 
     auto load_row = [&](int y, T (&dst)[V]) __attribute__((always_inline)) {
         if (clamp) {
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
         }
 
         T acc[P][V];
-        systolic_rows<T, V, P, Mask, false, C>(r, a.w, acc);
+        systolic_rows<T, V, P, Mask, false, C>(r, wts, acc, acc);
 
         if (lane_stores) {
 #pragma unroll

@@ -29,20 +29,24 @@ struct Args3D {
     T w[NW];
 };
 
-template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int U, int DZI>
+// One step of the z march: input plane `r` (z = zin) is added into the in-flight output
+// planes.  acc[k] holds output plane zin - RZ + k, which takes the stencil slice dz = RZ - k
+// of this input plane.  Each plane's sums are read from slot k+1 and written to slot k, so
+// the planes move one slot towards completion per step at no cost in instructions; the
+// newest plane (slot 2*RZ) starts from zero, and after the step slot 0 is complete.
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int K>
 struct PlaneStep {
-    // Adds input plane `r` (step index u within the unrolled group) into the in-flight planes.
-    static __device__ __forceinline__ void run(const T (&r)[P + 2 * RY][V], const T* __restrict__ w,
+    static __device__ __forceinline__ void run(const T (&r)[P + 2 * RY][V], ConstPtr<T> w,
                                                T (&acc)[2 * RZ + 1][P][V])
     {
         constexpr int NZ = 2 * RZ + 1;
-        constexpr int DZ = DZI - RZ;
-        constexpr int slot = ((U - DZ) % NZ + NZ) % NZ;
-        typedef SliceMask<RX, RY, RZ, BUDGET, DZ> Mask;
-        // dz = -RZ is the first contribution an output plane receives: assign, do not add
-        if constexpr (DZ == -RZ) systolic_rows<T, V, P, Mask, false, P + 2 * RY>(r, w, acc[slot]);
-        else systolic_rows<T, V, P, Mask, true, P + 2 * RY>(r, w, acc[slot]);
-        if constexpr (DZI + 1 < NZ) PlaneStep<T, V, P, RX, RY, RZ, BUDGET, U, DZI + 1>::run(r, w, acc);
+        typedef SliceMask<RX, RY, RZ, BUDGET, RZ - K> Mask;
+        if constexpr (K == NZ - 1) {
+            systolic_rows<T, V, P, Mask, false, P + 2 * RY>(r, w, acc[K], acc[K]);
+        } else {
+            systolic_rows<T, V, P, Mask, true, P + 2 * RY>(r, w, acc[K + 1], acc[K]);
+            PlaneStep<T, V, P, RX, RY, RZ, BUDGET, K + 1>::run(r, w, acc);
+        }
     }
 };
 
@@ -74,6 +78,8 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     const bool fast_x = vec_ok && xw0 >= 0 && xw0 + kWave * V <= W;
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
+    typedef Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> Args;
+    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
     const size_t plane = (size_t)W * H;
 
     auto load_plane = [&](int z, T (&dst)[C][V]) __attribute__((always_inline)) {
@@ -113,29 +119,25 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
 #pragma unroll
             for (int j = 0; j < V; ++j) acc[s][p][j] = T(0);
 
-    // Two plane buffers alternate (the next plane is requested before the current one is
-    // used, so its latency hides behind the arithmetic).  The march is unrolled over
-    // lcm(2, NZ) steps so that buffer parity and accumulator slots are compile-time.
-    constexpr int UNR = 2 * NZ;
+    // Two plane buffers alternate: the next plane is requested before the current one is
+    // used, so its latency hides behind the arithmetic.  The march is unrolled by two so the
+    // buffer in use is known at compile time.
     T buf[2][C][V];
     const int nt = (z1 - z0) + 2 * RZ;    // input planes z0-RZ .. z1-1+RZ
     load_plane(z0 - RZ, buf[0]);
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
 
-    for (int tb = 0; tb < nt; tb += UNR) {
-        static_for<UNR>([&](auto uc) __attribute__((always_inline)) {
-            constexpr int u = decltype(uc)::value;
-            constexpr int cur = u & 1;
-            constexpr int ubase = u % NZ;
-            const int t = tb + u;
+    for (int tb = 0; tb < nt; tb += 2) {
+        static_for<2>([&](auto uc) __attribute__((always_inline)) {
+            constexpr int cur = decltype(uc)::value;
+            const int t = tb + cur;
             if (t < nt) {
                 const int zin = z0 - RZ + t;
                 if (t + 1 < nt) load_plane(zin + 1, buf[cur ^ 1]);
-                PlaneStep<T, V, P, RX, RY, RZ, BUDGET, ubase, 0>::run(buf[cur], a.w, acc);
+                PlaneStep<T, V, P, RX, RY, RZ, BUDGET, 0>::run(buf[cur], wts, acc);
 
                 // output plane zin - RZ has now received its last contribution
                 const int zo = zin - RZ;
-                constexpr int slot = ((ubase - RZ) % NZ + NZ) % NZ;
                 if (zo >= z0 && lane_stores) {
 #pragma unroll
                     for (int p = 0; p < P; ++p) {
@@ -143,11 +145,11 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
                         if (y < H) {
                             T* rowp = a.out + (size_t)zo * plane + (size_t)y * W;
                             if (vec_ok) {
-                                store_vec<T, V>(rowp + xc, acc[slot][p]);
+                                store_vec<T, V>(rowp + xc, acc[0][p]);
                             } else {
 #pragma unroll
                                 for (int i = 0; i < V; ++i)
-                                    if (xc + i < W) rowp[xc + i] = acc[slot][p][i];
+                                    if (xc + i < W) rowp[xc + i] = acc[0][p][i];
                             }
                         }
                     }
@@ -200,7 +202,7 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
                 if (used > BUDGET) continue;
                 int idx;
                 if (BUDGET == 1) idx = k != RZ ? k : (n != RY ? NZ + n : (m != RX ? NZ + NY + m : RZ));
-                else idx = (k * NY + n) * NX + m;
+                else idx = (k * NX + m) * NY + n;
                 a.w[idx] = c[(k * NY + n) * NX + m];
             }
     hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET>), dim3(g.blocks), dim3(kBlock), 0,
