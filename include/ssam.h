@@ -94,8 +94,8 @@ const char *ssam_status_string(int status);
 
 /* Tuning override for experiments and benchmarks (not needed for correct use): sets a named
  * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
- * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic".  value < 0 restores the
- * built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
+ * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "nt_loads", "nt_stores".
+ * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 
 /* Planning query, host only (nothing is launched, no pointer is dereferenced except h_coef):

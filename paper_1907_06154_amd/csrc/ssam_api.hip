@@ -25,7 +25,7 @@ std::vector<Instance3D>& registry3d()
 namespace {
 
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
-    g_force_generic{-1};
+    g_force_generic{-1}, g_nt_loads{-1}, g_nt_stores{-1};
 
 Tuning current_tuning()
 {
@@ -35,6 +35,8 @@ Tuning current_tuning()
     t.planes_per_wave = g_planes_per_wave.load();
     t.xcd_remap = g_xcd_remap.load();
     t.force_generic = g_force_generic.load();
+    t.nt_loads = g_nt_loads.load();
+    t.nt_stores = g_nt_stores.load();
     return t;
 }
 
@@ -420,6 +422,8 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "planes_per_wave")) g_planes_per_wave = value;
     else if (!strcmp(name, "xcd_remap")) g_xcd_remap = value;
     else if (!strcmp(name, "force_generic")) g_force_generic = value;
+    else if (!strcmp(name, "nt_loads")) g_nt_loads = value;
+    else if (!strcmp(name, "nt_stores")) g_nt_stores = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

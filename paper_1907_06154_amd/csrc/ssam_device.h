@@ -75,31 +75,35 @@ template <> struct VecOf<float, 1> { typedef float type; };
 template <> struct VecOf<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
 template <> struct VecOf<double, 1> { typedef double type; };
 
+// `stream` selects the non-temporal (streaming) cache policy: the grid is far larger than the
+// caches and every output is written once and never read back by the same sweep.
 template <typename T, int V>
-__device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V])
+__device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V], bool stream)
 {
+    typedef typename VecOf<T, V>::type vec_t;
+    const vec_t* vp = reinterpret_cast<const vec_t*>(p);
+    const vec_t v = stream ? __builtin_nontemporal_load(vp) : *vp;
     if constexpr (V == 1) {
-        dst[0] = *p;
+        dst[0] = v;
     } else {
-        typedef typename VecOf<T, V>::type vec_t;
-        const vec_t v = *reinterpret_cast<const vec_t*>(p);
 #pragma unroll
         for (int i = 0; i < V; ++i) dst[i] = v[i];
     }
 }
 
 template <typename T, int V>
-__device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V])
+__device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V], bool stream)
 {
+    typedef typename VecOf<T, V>::type vec_t;
+    vec_t v;
     if constexpr (V == 1) {
-        *p = src[0];
+        v = src[0];
     } else {
-        typedef typename VecOf<T, V>::type vec_t;
-        vec_t v;
 #pragma unroll
         for (int i = 0; i < V; ++i) v[i] = src[i];
-        *reinterpret_cast<vec_t*>(p) = v;
     }
+    if (stream) __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+    else *reinterpret_cast<vec_t*>(p) = v;
 }
 
 // ---- tap masks ------------------------------------------------------------------------

@@ -20,6 +20,8 @@ struct Tuning {
     int planes_per_wave = -1;  // 3D: output planes one wave marches over
     int xcd_remap = -1;        // 1: consecutive logical blocks share an XCD
     int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
+    int nt_loads = -1;         // 1: grid loads use the streaming cache policy
+    int nt_stores = -1;        // 1: grid stores use the streaming cache policy
 };
 
 struct Problem2D {

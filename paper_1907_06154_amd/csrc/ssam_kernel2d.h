@@ -25,7 +25,8 @@ struct Args2D {
     int rows_per_wave;  // multiple of P
     int blocks;         // launched blocks
     int xcd_remap;
-    int aligned;        // both base pointers are aligned to V elements
+    int aligned;
+    int nt_loads, nt_stores;   // streaming cache policy for grid loads / stores        // both base pointers are aligned to V elements
     T w[NW];            // packed per Mask::widx, read through scalar loads (wave-uniform broadcast, Sec. 4.6)
 };
 
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
         }
         const T* rowp = in + (size_t)y * W;
         if (fast_x) {
-            load_vec<T, V>(rowp + xc, dst);
+            load_vec<T, V>(rowp + xc, dst, a.nt_loads);
         } else {
 #pragma unroll
             for (int i = 0; i < V; ++i) {
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
                 if (y + p < y1) {
                     T* rowp = a.out + (size_t)(y + p) * W;
                     if (vec_ok) {
-                        store_vec<T, V>(rowp + xc, acc[p]);
+                        store_vec<T, V>(rowp + xc, acc[p], a.nt_stores);
                     } else {
 #pragma unroll
                         for (int i = 0; i < V; ++i)
@@ -153,6 +154,8 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     a.blocks = g.blocks;
     a.xcd_remap = g.xcd_remap;
     a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
+    a.nt_loads = tu.nt_loads < 0 ? 0 : tu.nt_loads;
+    a.nt_stores = tu.nt_stores < 0 ? 1 : tu.nt_stores;
     const T* w = static_cast<const T*>(pr.w);   // host, dense [N][M]
     for (int n = 0; n < N; ++n)
         for (int m = 0; m < M; ++m)

@@ -26,6 +26,7 @@ struct Args3D {
     int blocks;
     int xcd_remap;
     int aligned;
+    int nt_loads, nt_stores;   // streaming cache policy for grid loads / stores
     T w[NW];
 };
 
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
             }
             const T* rowp = in + (size_t)z * plane + (size_t)y * W;
             if (fast_x) {
-                load_vec<T, V>(rowp + xc, dst[k]);
+                load_vec<T, V>(rowp + xc, dst[k], a.nt_loads);
             } else {
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
                         if (y < H) {
                             T* rowp = a.out + (size_t)zo * plane + (size_t)y * W;
                             if (vec_ok) {
-                                store_vec<T, V>(rowp + xc, acc[0][p]);
+                                store_vec<T, V>(rowp + xc, acc[0][p], a.nt_stores);
                             } else {
 #pragma unroll
                                 for (int i = 0; i < V; ++i)
@@ -193,6 +194,8 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     a.blocks = g.blocks;
     a.xcd_remap = g.xcd_remap;
     a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
+    a.nt_loads = tu.nt_loads < 0 ? 0 : tu.nt_loads;
+    a.nt_stores = tu.nt_stores < 0 ? 1 : tu.nt_stores;
     const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
     for (int i = 0; i < Mask0::kNW; ++i) a.w[i] = T(0);
     for (int k = 0; k < NZ; ++k)
