@@ -25,7 +25,7 @@ std::vector<Instance3D>& registry3d()
 namespace {
 
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
-    g_force_generic{-1}, g_nt_loads{-1}, g_nt_stores{-1};
+    g_force_generic{-1}, g_variant{-1};
 
 Tuning current_tuning()
 {
@@ -35,8 +35,7 @@ Tuning current_tuning()
     t.planes_per_wave = g_planes_per_wave.load();
     t.xcd_remap = g_xcd_remap.load();
     t.force_generic = g_force_generic.load();
-    t.nt_loads = g_nt_loads.load();
-    t.nt_stores = g_nt_stores.load();
+    t.variant = g_variant.load();
     return t;
 }
 
@@ -208,7 +207,7 @@ struct Choice2D {
 };
 
 template <typename T>
-const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics)
+const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant)
 {
     const T* w = static_cast<const T*>(p.w);
     int budget = 2;
@@ -221,6 +220,7 @@ const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics)
         if (i.dtype != p.dtype || i.M != p.M || i.N != p.N || i.AX != p.ax) continue;
         if (i.budget < budget) continue;
         if (i.budget == 1 && p.ay != p.N / 2) continue;   // star instances assume the centre row
+        if (i.variant != want_variant) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
@@ -231,7 +231,12 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
     const Tuning tu = current_tuning();
     const Instance2D* inst = nullptr;
     if (tu.force_generic <= 0)
-        inst = p.dtype == SSAM_F32 ? pick2d<float>(p, stencil_semantics) : pick2d<double>(p, stencil_semantics);
+    {
+        const int v = tu.variant > 0 ? tu.variant : 0;
+        inst = p.dtype == SSAM_F32 ? pick2d<float>(p, stencil_semantics, v) : pick2d<double>(p, stencil_semantics, v);
+        if (!inst && v != 0)   // no such alternative for this shape: use the default instance
+            inst = p.dtype == SSAM_F32 ? pick2d<float>(p, stencil_semantics, 0) : pick2d<double>(p, stencil_semantics, 0);
+    }
     if (inst) {
         if (name) *name = inst->name;
         return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
@@ -255,7 +260,7 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
 }
 
 template <typename T>
-const Instance3D* pick3d(const Problem3D& p)
+const Instance3D* pick3d(const Problem3D& p, int want_variant)
 {
     const T* c = static_cast<const T*>(p.c);
     int budget = tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
@@ -263,6 +268,7 @@ const Instance3D* pick3d(const Problem3D& p)
     const Instance3D* best = nullptr;
     for (const Instance3D& i : registry3d()) {
         if (i.dtype != p.dtype || i.rx != p.rx || i.ry != p.ry || i.rz != p.rz || i.budget < budget) continue;
+        if (i.variant != want_variant) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
@@ -276,7 +282,11 @@ int run3d(const Problem3D& p, Geometry* geo, bool dry, std::string* name)
         return run2d(q, true, geo, dry, name);
     }
     const Instance3D* inst = nullptr;
-    if (tu.force_generic <= 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p) : pick3d<double>(p);
+    if (tu.force_generic <= 0) {
+        const int v = tu.variant > 0 ? tu.variant : 0;
+        inst = p.dtype == SSAM_F32 ? pick3d<float>(p, v) : pick3d<double>(p, v);
+        if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p, 0) : pick3d<double>(p, 0);
+    }
     if (inst) {
         if (name) *name = inst->name;
         return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
@@ -422,8 +432,7 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "planes_per_wave")) g_planes_per_wave = value;
     else if (!strcmp(name, "xcd_remap")) g_xcd_remap = value;
     else if (!strcmp(name, "force_generic")) g_force_generic = value;
-    else if (!strcmp(name, "nt_loads")) g_nt_loads = value;
-    else if (!strcmp(name, "nt_stores")) g_nt_stores = value;
+    else if (!strcmp(name, "variant")) g_variant = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

@@ -75,14 +75,20 @@ template <> struct VecOf<float, 1> { typedef float type; };
 template <> struct VecOf<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
 template <> struct VecOf<double, 1> { typedef double type; };
 
-// `stream` selects the non-temporal (streaming) cache policy: the grid is far larger than the
-// caches and every output is written once and never read back by the same sweep.
-template <typename T, int V>
-__device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V], bool stream)
+// STREAM selects the non-temporal (streaming) cache policy at compile time: the grid is far
+// larger than the caches and every output is written once and never read back by the same
+// sweep.  (A run-time choice between the two forms is folded into the plain one by the
+// compiler, which drops the hint.)
+constexpr int kStreamLoads = 1, kStreamStores = 2;
+
+template <typename T, int V, bool STREAM>
+__device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V])
 {
     typedef typename VecOf<T, V>::type vec_t;
     const vec_t* vp = reinterpret_cast<const vec_t*>(p);
-    const vec_t v = stream ? __builtin_nontemporal_load(vp) : *vp;
+    vec_t v;
+    if constexpr (STREAM) v = __builtin_nontemporal_load(vp);
+    else v = *vp;
     if constexpr (V == 1) {
         dst[0] = v;
     } else {
@@ -91,8 +97,8 @@ __device__ __forceinline__ void load_vec(const T* __restrict__ p, T (&dst)[V], b
     }
 }
 
-template <typename T, int V>
-__device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V], bool stream)
+template <typename T, int V, bool STREAM>
+__device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V])
 {
     typedef typename VecOf<T, V>::type vec_t;
     vec_t v;
@@ -102,7 +108,7 @@ __device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V], 
 #pragma unroll
         for (int i = 0; i < V; ++i) v[i] = src[i];
     }
-    if (stream) __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+    if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
     else *reinterpret_cast<vec_t*>(p) = v;
 }
 

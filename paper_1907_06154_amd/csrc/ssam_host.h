@@ -20,8 +20,7 @@ struct Tuning {
     int planes_per_wave = -1;  // 3D: output planes one wave marches over
     int xcd_remap = -1;        // 1: consecutive logical blocks share an XCD
     int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
-    int nt_loads = -1;         // 1: grid loads use the streaming cache policy
-    int nt_stores = -1;        // 1: grid stores use the streaming cache policy
+    int variant = -1;          // pick an alternative compiled instance of the same shape
 };
 
 struct Problem2D {
@@ -65,12 +64,14 @@ typedef hipError_t (*Launch3DFn)(const Problem3D&, const Tuning&, Geometry*, boo
 struct Instance2D {
     const char* name;
     int dtype, M, N, AX, budget;  // budget 2 = dense box, 1 = star
+    int variant;                  // 0 = default instance for the shape
     Launch2DFn launch;
 };
 
 struct Instance3D {
     const char* name;
     int dtype, rx, ry, rz, budget;  // budget = max number of non-zero offset components (1 star, 2, 3 box)
+    int variant;
     Launch3DFn launch;
 };
 

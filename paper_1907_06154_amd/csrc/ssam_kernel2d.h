@@ -30,7 +30,7 @@ struct Args2D {
     T w[NW];            // packed per Mask::widx, read through scalar loads (wave-uniform broadcast, Sec. 4.6)
 };
 
-template <typename T, int V, int P, class Mask>
+template <typename T, int V, int P, class Mask, bool PREFETCH, int NT>
 __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kNW> a)
 {
     constexpr int N = Mask::kN;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
         }
         const T* rowp = in + (size_t)y * W;
         if (fast_x) {
-            load_vec<T, V>(rowp + xc, dst, a.nt_loads);
+            load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xc, dst);
         } else {
 #pragma unroll
             for (int i = 0; i < V; ++i) {
@@ -79,23 +79,33 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
         }
     };
 
+    // PREFETCH: the next P rows are requested into a second buffer before the current ones
+    // are used (latency hidden inside the wave, at the price of P*V more registers);
+    // otherwise rows are loaded straight into the cache and other waves hide the latency.
     T r[C][V];
-    T nxt[P][V];
+    T nxt[PREFETCH ? P : 1][V];
 #pragma unroll
     for (int k = 0; k < N - 1; ++k) load_row(y0 - a.ay + k, r[k]);
+    if constexpr (PREFETCH) {
 #pragma unroll
-    for (int k = 0; k < P; ++k) load_row(y0 - a.ay + N - 1 + k, nxt[k]);
+        for (int k = 0; k < P; ++k) load_row(y0 - a.ay + N - 1 + k, nxt[k]);
+    }
 
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
 
     for (int y = y0; y < y1; y += P) {
+        if constexpr (PREFETCH) {
 #pragma unroll
-        for (int k = 0; k < P; ++k)
+            for (int k = 0; k < P; ++k)
 #pragma unroll
-            for (int i = 0; i < V; ++i) r[N - 1 + k][i] = nxt[k][i];
-        if (y + P < y1) {
+                for (int i = 0; i < V; ++i) r[N - 1 + k][i] = nxt[k][i];
+            if (y + P < y1) {
 #pragma unroll
-            for (int k = 0; k < P; ++k) load_row(y + P - a.ay + N - 1 + k, nxt[k]);
+                for (int k = 0; k < P; ++k) load_row(y + P - a.ay + N - 1 + k, nxt[k]);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < P; ++k) load_row(y - a.ay + N - 1 + k, r[N - 1 + k]);
         }
 
         T acc[P][V];
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
                 if (y + p < y1) {
                     T* rowp = a.out + (size_t)(y + p) * W;
                     if (vec_ok) {
-                        store_vec<T, V>(rowp + xc, acc[p], a.nt_stores);
+                        store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[p]);
                     } else {
 #pragma unroll
                         for (int i = 0; i < V; ++i)
@@ -123,7 +133,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
     }
 }
 
-template <typename T, int V, int P, class Mask>
+template <typename T, int V, int P, class Mask, bool PREFETCH, int NT>
 hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     constexpr int M = Mask::kM, N = Mask::kN;
@@ -154,20 +164,22 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     a.blocks = g.blocks;
     a.xcd_remap = g.xcd_remap;
     a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
-    a.nt_loads = tu.nt_loads < 0 ? 0 : tu.nt_loads;
-    a.nt_stores = tu.nt_stores < 0 ? 1 : tu.nt_stores;
     const T* w = static_cast<const T*>(pr.w);   // host, dense [N][M]
     for (int n = 0; n < N; ++n)
         for (int m = 0; m < M; ++m)
             if (Mask::tap(n, m)) a.w[Mask::widx(n, m)] = w[n * M + m];
-    hipLaunchKernelGGL((ssam2d_kernel<T, V, P, Mask>), dim3(g.blocks), dim3(kBlock), 0, pr.stream, a);
+    hipLaunchKernelGGL((ssam2d_kernel<T, V, P, Mask, PREFETCH, NT>), dim3(g.blocks), dim3(kBlock), 0, pr.stream, a);
     return hipGetLastError();
 }
 
-// Registers ssam2d_kernel<T, V, P, TapMask<M, N, AX, N/2, BUDGET>> under the dispatcher.
-#define SSAM_INSTANCE_2D(T, DT, V, P, M, N, AX, BUDGET)                                              \
+// Registers ssam2d_kernel<T, V, P, TapMask<M, N, AX, N/2, BUDGET>, PREFETCH, NT> under the
+// dispatcher.  NT: bit 0 = streaming loads, bit 1 = streaming stores.  VARIANT 0 is the
+// instance used by default; others are alternatives selectable for tuning.
+#define SSAM_INSTANCE_2D_V(T, DT, V, P, M, N, AX, BUDGET, PREFETCH, NT, VARIANT)                     \
     static ::ssam::Register2D SSAM_CAT(reg2d_, __COUNTER__)(::ssam::Instance2D{                      \
-        #T "_M" #M "N" #N "_b" #BUDGET "_v" #V "p" #P, DT, M, N, AX, BUDGET,                         \
-        &::ssam::launch2d<T, V, P, ::ssam::TapMask<M, N, AX, (N) / 2, BUDGET>>})
+        #T "_M" #M "N" #N "_b" #BUDGET "_v" #V "p" #P "f" #PREFETCH "nt" #NT, DT, M, N, AX, BUDGET,   \
+        VARIANT,                                                                                      \
+        &::ssam::launch2d<T, V, P, ::ssam::TapMask<M, N, AX, (N) / 2, BUDGET>, (PREFETCH) != 0, NT>})
+#define SSAM_INSTANCE_2D(T, DT, V, P, M, N, AX, BUDGET) SSAM_INSTANCE_2D_V(T, DT, V, P, M, N, AX, BUDGET, 1, 2, 0)
 
 }  // namespace ssam

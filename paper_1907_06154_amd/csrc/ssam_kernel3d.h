@@ -26,7 +26,6 @@ struct Args3D {
     int blocks;
     int xcd_remap;
     int aligned;
-    int nt_loads, nt_stores;   // streaming cache policy for grid loads / stores
     T w[NW];
 };
 
@@ -51,7 +50,7 @@ struct PlaneStep {
     }
 };
 
-template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET>
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT>
 __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     const Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> a)
 {
@@ -100,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
             }
             const T* rowp = in + (size_t)z * plane + (size_t)y * W;
             if (fast_x) {
-                load_vec<T, V>(rowp + xc, dst[k], a.nt_loads);
+                load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xc, dst[k]);
             } else {
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
                         if (y < H) {
                             T* rowp = a.out + (size_t)zo * plane + (size_t)y * W;
                             if (vec_ok) {
-                                store_vec<T, V>(rowp + xc, acc[0][p], a.nt_stores);
+                                store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[0][p]);
                             } else {
 #pragma unroll
                                 for (int i = 0; i < V; ++i)
@@ -160,7 +159,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     }
 }
 
-template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET>
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT>
 hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
@@ -194,8 +193,6 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     a.blocks = g.blocks;
     a.xcd_remap = g.xcd_remap;
     a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
-    a.nt_loads = tu.nt_loads < 0 ? 0 : tu.nt_loads;
-    a.nt_stores = tu.nt_stores < 0 ? 1 : tu.nt_stores;
     const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
     for (int i = 0; i < Mask0::kNW; ++i) a.w[i] = T(0);
     for (int k = 0; k < NZ; ++k)
@@ -208,14 +205,15 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
                 else idx = (k * NX + m) * NY + n;
                 a.w[idx] = c[(k * NY + n) * NX + m];
             }
-    hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET>), dim3(g.blocks), dim3(kBlock), 0,
+    hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET, NT>), dim3(g.blocks), dim3(kBlock), 0,
                        pr.stream, a);
     return hipGetLastError();
 }
 
-#define SSAM_INSTANCE_3D(T, DT, V, P, RX, RY, RZ, BUDGET)                                            \
+#define SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, NT, VARIANT)                              \
     static ::ssam::Register3D SSAM_CAT(reg3d_, __COUNTER__)(::ssam::Instance3D{                      \
-        #T "_r" #RX #RY #RZ "_b" #BUDGET "_v" #V "p" #P, DT, RX, RY, RZ, BUDGET,                     \
-        &::ssam::launch3d<T, V, P, RX, RY, RZ, BUDGET>})
+        #T "_r" #RX #RY #RZ "_b" #BUDGET "_v" #V "p" #P "nt" #NT, DT, RX, RY, RZ, BUDGET, VARIANT,    \
+        &::ssam::launch3d<T, V, P, RX, RY, RZ, BUDGET, NT>})
+#define SSAM_INSTANCE_3D(T, DT, V, P, RX, RY, RZ, BUDGET) SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, 2, 0)
 
 }  // namespace ssam
