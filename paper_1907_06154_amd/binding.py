@@ -13,7 +13,7 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libssam.so")
+LIB_PATH = os.environ.get("SSAM_LIB_PATH") or os.path.join(_HERE, "libssam.so")   # override: A/B builds
 _lib: Optional[ctypes.CDLL] = None
 
 SSAM_F32, SSAM_F64 = 0, 1

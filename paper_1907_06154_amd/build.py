@@ -28,22 +28,27 @@ def _compile(src: str, extra) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{res.stdout}\n{res.stderr}")
-    if res.stderr.strip():
-        sys.stderr.write(res.stderr)
+    noise = "is not a recognized feature for this target"   # host pass does not know the device feature
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if err.strip():
+        sys.stderr.write(err + "\n")
     return obj
 
 
-def build(verbose: bool = False, jobs: int = 8, extra=()) -> str:
+def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB) -> str:
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(lambda s: _compile(s, list(extra)), srcs))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
     if verbose:
-        print(f"built {LIB} from {len(srcs)} translation units")
-    return LIB
+        print(f"built {lib} from {len(srcs)} translation units")
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    # python -m paper_1907_06154_amd.build [output.so] [-DNAME ...]   (extra defines: experiments)
+    args = sys.argv[1:]
+    out = next((a for a in args if a.endswith(".so")), LIB)
+    build(verbose=True, extra=[a for a in args if a.startswith("-D")], lib=out)

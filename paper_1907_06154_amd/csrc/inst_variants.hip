@@ -1,15 +1,19 @@
 // Alternative instances of shapes that also have a default instance: selectable with the
-// "variant" tuning knob, used to compare cache policy, register-cache depth (P) and in-wave
-// prefetch.
+// "variant" tuning knob, used to compare cache policy, register-cache depth (P), columns per
+// lane (V) and in-wave prefetch.
 #include "ssam_kernel2d.h"
 #include "ssam_kernel3d.h"
 
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 3, 1, 2, 1, 0, 1);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 3, 1, 2, 1, 1, 2);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 3, 1, 2, 1, 2, 3);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 0, 3, 4);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 3, 1, 2, 0, 3, 5);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 1, 3, 6);
-SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 0, 1);
-SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 1, 2);
-SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 2, 3);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 3, 1, 2, 0, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 1, 2, 2);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 0, 2, 3);
+SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 0, 2, 1);
+SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 3, 1, 2, 1);
+SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 4, 4, 4, 1, 1, 2, 1);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 4, 4, 4, 4, 4, 1, 0, 2, 1);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 4, 4, 4, 1, 0, 2, 2);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 8, 4, 4, 4, 1, 0, 2, 3);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 1, 1, 1, 1, 1, 2, 1);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 1, 1, 1, 3, 1, 2, 1);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 4, 4, 1, 1, 1, 1, 0, 2, 2);
+SSAM_INSTANCE_3D_V(float, SSAM_F32, 4, 4, 1, 1, 1, 3, 0, 2, 2);

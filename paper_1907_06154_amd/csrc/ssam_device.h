@@ -112,6 +112,32 @@ __device__ __forceinline__ void store_vec(T* __restrict__ p, const T (&src)[V])
     else *reinterpret_cast<vec_t*>(p) = v;
 }
 
+// ---- branch-free boundary fix-ups --------------------------------------------------------
+// keep_if(v, m): v where the 32-bit mask m is all ones, +0 where it is zero.
+// pick(a, b, m): b where m is all ones, a where it is zero (v_bfi_b32).
+// Written on the bit patterns so the compiler cannot turn them into divergent branches
+// around the loads they follow (which would serialise the loads of a tile's rows).
+__device__ __forceinline__ float keep_if(float v, unsigned m) { return __builtin_bit_cast(float, __builtin_bit_cast(unsigned, v) & m); }
+__device__ __forceinline__ double keep_if(double v, unsigned m)
+{
+    Halves h = __builtin_bit_cast(Halves, v);
+    h.lo &= (int)m;
+    h.hi &= (int)m;
+    return __builtin_bit_cast(double, h);
+}
+__device__ __forceinline__ unsigned pick_bits(unsigned a, unsigned b, unsigned m) { return (b & m) | (a & ~m); }
+__device__ __forceinline__ float pick(float a, float b, unsigned m)
+{
+    return __builtin_bit_cast(float, pick_bits(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), m));
+}
+__device__ __forceinline__ double pick(double a, double b, unsigned m)
+{
+    Halves x = __builtin_bit_cast(Halves, a), y = __builtin_bit_cast(Halves, b);
+    x.lo = (int)pick_bits((unsigned)x.lo, (unsigned)y.lo, m);
+    x.hi = (int)pick_bits((unsigned)x.hi, (unsigned)y.hi, m);
+    return __builtin_bit_cast(double, x);
+}
+
 // ---- tap masks ------------------------------------------------------------------------
 // Coefficients are run-time data; only the *shape* is compiled in, as in the paper's
 // one-instance-per-(M,N) template.  A mask describes one filter slice of width M (x) and
@@ -180,11 +206,27 @@ __device__ __forceinline__ int opaque_zero()
     return z;
 }
 
+// Views of the register cache handed to the row evaluation.  Row and column indices are
+// compile-time constants after unrolling, so at(k, i) names one register.
+template <typename T, int V, int ROWS>
+struct RowBlock {               // one array of ROWS cached rows
+    static constexpr int kRows = ROWS;
+    const T (&r)[ROWS][V];
+    __device__ __forceinline__ T at(int k, int i) const { return r[k][i]; }
+};
+template <typename T, int V, int HEAD, int TAIL>
+struct RowPair {                // HEAD rows kept from the previous window, then TAIL new rows
+    static constexpr int kRows = HEAD + TAIL;
+    const T (&head)[HEAD > 0 ? HEAD : 1][V];
+    const T (&tail)[TAIL][V];
+    __device__ __forceinline__ T at(int k, int i) const { return k < HEAD ? head[k < HEAD ? k : 0][i] : tail[k >= HEAD ? k - HEAD : 0][i]; }
+};
+
 // Products of one filter column, for all P window positions: the lane's own column i = j + COL
 // multiplies filter column AX + DX and accumulates into the partial sum of output column j.
 // (Sec. 4.3: an N-term inner product between a register vector and a filter column.)
-template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, int ROWS>
-__device__ __forceinline__ void column_products(const T (&r)[ROWS][V], ConstPtr<T> w, T (&s)[P][V])
+template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, class Rows>
+__device__ __forceinline__ void column_products(const Rows& r, ConstPtr<T> w, T (&s)[P][V])
 {
     constexpr int N = Mask::kN, AX = Mask::kAX;
     const int z = PIN ? opaque_zero() : 0;
@@ -197,17 +239,33 @@ __device__ __forceinline__ void column_products(const T (&r)[ROWS][V], ConstPtr<
                 const int i = j + COL;
                 if (i >= 0 && i < V) {
 #pragma unroll
-                    for (int p = 0; p < P; ++p) s[p][j] = fma_t(r[p + n][i], wv, s[p][j]);
+                    for (int p = 0; p < P; ++p) s[p][j] = fma_t(r.at(p + n, i), wv, s[p][j]);
                 }
             }
         }
     }
 }
 
+// Has the partial sum of output column j received any product by the time it leaves the lane
+// at distance d from its owner?  (side -1: the chain coming from the left, whose taps lie
+// `reach` columns to the left at most; +1: from the right.)  Sums that are still exactly zero
+// are not shifted: with V columns per lane only the outputs near the lane's edge depend on
+// the neighbouring lane when the filter is narrow (Sec. 5.4: fewer horizontal transfers).
+template <int V>
+__host__ __device__ constexpr bool chain_touches(int j, int d, int dmax, int reach, int side)
+{
+    for (int dd = d; dd <= dmax; ++dd)
+        for (int i = 0; i < V; ++i) {
+            const int dx = side < 0 ? i - j - dd * V : i - j + dd * V;
+            if (side < 0 ? (dx >= -reach && dx <= -1) : (dx >= 1 && dx <= reach)) return true;
+        }
+    return false;
+}
+
 // For P window positions p (the sliding window of Sec. 4.2) computes
 //     out[p][j] = (ACCUMULATE ? in[p][j] : 0) + sum over taps (n, m) of
 //                 w[widx(n, m)] * column(x_j + m - AX)[p + n]
-// where lane L's register cache r[k][i] holds row k of its own column L*V + i, and x_j is
+// where lane L's register cache r.at(k, i) holds row k of its own column L*V + i, and x_j is
 // the lane's own column j: the result lands in the lane that owns the output column, so
 // loads and stores are both V-aligned.  `in` and `out` may be different arrays (the 3D march
 // uses that to rotate its in-flight planes for free) or the same one.
@@ -220,12 +278,12 @@ __device__ __forceinline__ void column_products(const T (&r)[ROWS][V], ConstPtr<
 // ceil(kRight/V) shifts the owner adds the columns it holds itself.  Lanes nearer than
 // ceil(kLeft/V) to the low end of the wave, or ceil(kRight/V) to the high end, end with
 // incomplete sums: they are the overlapped-blocking halo (Sec. 4.5).
-template <typename T, int V, int P, class Mask, bool ACCUMULATE, int ROWS>
-__device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], ConstPtr<T> w,
+template <typename T, int V, int P, class Mask, bool ACCUMULATE, class Rows>
+__device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
                                               const T (&in)[P][V], T (&out)[P][V])
 {
     constexpr int N = Mask::kN;
-    static_assert(ROWS >= N + P - 1, "register cache too small for the sliding window");
+    static_assert(Rows::kRows >= N + P - 1, "register cache too small for the sliding window");
     constexpr int DL = (Mask::kLeft + V - 1) / V;
     constexpr int DR = (Mask::kRight + V - 1) / V;
     constexpr bool PIN = Mask::kNW > 64;   // small coefficient sets stay resident in scalar registers
@@ -252,17 +310,21 @@ __device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], ConstPtr<T>
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) - d * V;
                 if constexpr (dx >= -Mask::kLeft && dx <= -1)
-                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, ROWS>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, Rows>(r, w, s);
             });
 #pragma unroll
             for (int p = 0; p < P; ++p)
 #pragma unroll
-                for (int j = 0; j < V; ++j) s[p][j] = shift_up(s[p][j]);
+                for (int j = 0; j < V; ++j)
+                    if (chain_touches<V>(j, d, DL, Mask::kLeft, -1)) s[p][j] = shift_up(s[p][j]);
         });
 #pragma unroll
         for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int j = 0; j < V; ++j) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+            for (int j = 0; j < V; ++j) {
+                if (chain_touches<V>(j, 1, DL, Mask::kLeft, -1)) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+                else if (!have) sum[p][j] = T(0);
+            }
         have = true;
     }
     // chain arriving from the right (higher lane ids)
@@ -277,17 +339,21 @@ __device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], ConstPtr<T>
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) + d * V;
                 if constexpr (dx >= 1 && dx <= Mask::kRight)
-                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, ROWS>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, Rows>(r, w, s);
             });
 #pragma unroll
             for (int p = 0; p < P; ++p)
 #pragma unroll
-                for (int j = 0; j < V; ++j) s[p][j] = shift_down(s[p][j]);
+                for (int j = 0; j < V; ++j)
+                    if (chain_touches<V>(j, d, DR, Mask::kRight, +1)) s[p][j] = shift_down(s[p][j]);
         });
 #pragma unroll
         for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int j = 0; j < V; ++j) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+            for (int j = 0; j < V; ++j) {
+                if (chain_touches<V>(j, 1, DR, Mask::kRight, +1)) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
+                else if (!have) sum[p][j] = T(0);
+            }
         have = true;
     }
     if (!have) {
@@ -300,7 +366,7 @@ __device__ __forceinline__ void systolic_rows(const T (&r)[ROWS][V], ConstPtr<T>
     static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
         constexpr int dx = decltype(cc)::value - (V - 1);
         if constexpr (dx >= -Mask::kLeft && dx <= Mask::kRight)
-            column_products<T, V, P, Mask, dx, dx, PIN, ROWS>(r, w, sum);
+            column_products<T, V, P, Mask, dx, dx, PIN, Rows>(r, w, sum);
     });
 #pragma unroll
     for (int p = 0; p < P; ++p)

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
 {
     constexpr int N = Mask::kN;
     constexpr int HL = (Mask::kLeft + V - 1) / V;
-    constexpr int C = N + P - 1;   // cached rows per lane (paper Eq. 3)
+    constexpr int HR = (Mask::kRight + V - 1) / V;
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -52,85 +52,136 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
     const int y0 = ytile * a.rows_per_wave;
     const int y1 = min(y0 + a.rows_per_wave, H);
     const bool vec_ok = a.aligned && (W % V) == 0;   // row starts stay V-aligned
-    const bool fast_x = vec_ok && xw0 >= 0 && xw0 + kWave * V <= W;   // wave-uniform
+    // lanes past the right halo hold nothing any stored output depends on: they re-read the last
+    // needed lane's columns (same cache line, no extra traffic, no divergence)
+    const int used_lanes = min(HL + a.valid_lanes + HR, kWave);
+    const int xl = xw0 + min(lane, used_lanes - 1) * V;   // first column this lane loads
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
     typedef Args2D<T, Mask::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
-
-    auto load_row = [&](int y, T (&dst)[V]) __attribute__((always_inline)) {
-        if (clamp) {
-            y = min(max(y, 0), H - 1);
-        } else if (y < 0 || y >= H) {
-#pragma unroll
-            for (int i = 0; i < V; ++i) dst[i] = T(0);
-            return;
-        }
-        const T* rowp = in + (size_t)y * W;
-        if (fast_x) {
-            load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xc, dst);
-        } else {
-#pragma unroll
-            for (int i = 0; i < V; ++i) {
-                const int x = xc + i;
-                if (clamp) dst[i] = rowp[min(max(x, 0), W - 1)];
-                else dst[i] = (x >= 0 && x < W) ? rowp[x] : T(0);
-            }
-        }
-    };
-
-    // PREFETCH: the next P rows are requested into a second buffer before the current ones
-    // are used (latency hidden inside the wave, at the price of P*V more registers);
-    // otherwise rows are loaded straight into the cache and other waves hide the latency.
-    T r[C][V];
-    T nxt[PREFETCH ? P : 1][V];
-#pragma unroll
-    for (int k = 0; k < N - 1; ++k) load_row(y0 - a.ay + k, r[k]);
-    if constexpr (PREFETCH) {
-#pragma unroll
-        for (int k = 0; k < P; ++k) load_row(y0 - a.ay + N - 1 + k, nxt[k]);
-    }
-
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
+    // per-lane column masks for the general path (a lane's V columns are all inside or all outside
+    // the grid when rows are V-aligned)
+    const unsigned left_mask = xc < 0 ? ~0u : 0u, right_mask = xc >= W ? ~0u : 0u;
+    const unsigned left_pick = clamp ? left_mask : 0u, right_pick = clamp ? right_mask : 0u;
+    const unsigned keep_cols = clamp ? ~0u : ~(left_mask | right_mask);
+    const unsigned keep_rows = clamp ? ~0u : 0u;   // mask applied to a row outside the grid
 
-    for (int y = y0; y < y1; y += P) {
-        if constexpr (PREFETCH) {
-#pragma unroll
-            for (int k = 0; k < P; ++k)
-#pragma unroll
-                for (int i = 0; i < V; ++i) r[N - 1 + k][i] = nxt[k][i];
-            if (y + P < y1) {
-#pragma unroll
-                for (int k = 0; k < P; ++k) load_row(y + P - a.ay + N - 1 + k, nxt[k]);
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < P; ++k) load_row(y - a.ay + N - 1 + k, r[N - 1 + k]);
-        }
+    // A tile is "interior" when every row and column it touches lies inside the grid and can be
+    // accessed as aligned vectors: then loads and stores need no check at all.  Every other
+    // tile takes the general path, which applies the boundary rule (wave-uniform row logic,
+    // per-lane selects for columns) and also serves grids whose rows are not V-aligned.
+    const int nchunks = (y1 - y0 + P - 1) / P;
+    const bool interior = vec_ok && xw0 >= 0 && xw0 + used_lanes * V <= W && (y1 - y0) % P == 0 &&
+                          y0 - a.ay >= 0 && y0 + nchunks * P - 1 - a.ay + N - 1 < H;
 
-        T acc[P][V];
-        systolic_rows<T, V, P, Mask, false, C>(r, wts, acc, acc);
+    auto march = [&](auto mode_tag) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode_tag)::value;   // 0 interior, 1 general with vectors, 2 general by element
+        constexpr bool EDGE = MODE != 0;
+        constexpr bool VEC = MODE != 2;
 
-        if (lane_stores) {
+        auto load_row = [&](int y, T (&dst)[V]) __attribute__((always_inline)) {
+            if constexpr (!EDGE) {
+                load_vec<T, V, (NT & kStreamLoads) != 0>(in + (size_t)y * W + xl, dst);
+            } else {
+                const bool row_in = y >= 0 && y < H;          // wave-uniform
+                const int yy = min(max(y, 0), H - 1);
+                const T* rowp = in + (size_t)yy * W;
+                if constexpr (VEC) {
+                    // x: W and xc are multiples of V, so a lane's V columns are all in or all out
+                    const int xv = min(max(xl, 0), W - V);
+                    load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xv, dst);
+                    // one branch-free sequence serves both rules: clamp replaces out-of-grid
+                    // columns by the edge column, zero padding blanks them (and whole rows)
+                    const T first = dst[0], last = dst[V - 1];
+                    const unsigned keep = keep_cols & (row_in ? ~0u : keep_rows);
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-                if (y + p < y1) {
-                    T* rowp = a.out + (size_t)(y + p) * W;
-                    if (vec_ok) {
-                        store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[p]);
-                    } else {
+                    for (int i = 0; i < V; ++i)
+                        dst[i] = keep_if(pick(pick(dst[i], first, left_pick), last, right_pick), keep);
+                } else {
 #pragma unroll
-                        for (int i = 0; i < V; ++i)
-                            if (xc + i < W) rowp[xc + i] = acc[p][i];
+                    for (int i = 0; i < V; ++i) {
+                        const int x = xc + i;
+                        const T v = rowp[min(max(x, 0), W - 1)];
+                        dst[i] = (clamp || (row_in && x >= 0 && x < W)) ? v : T(0);
                     }
                 }
             }
+        };
+
+        auto store_rows = [&](int y, const T (&acc)[P][V]) __attribute__((always_inline)) {
+            if (lane_stores) {
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    T* rowp = a.out + (size_t)(y + p) * W;
+                    if constexpr (!EDGE) {
+                        store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[p]);
+                    } else if (y + p < y1) {
+                        if constexpr (VEC) {
+                            store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[p]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < V; ++i)
+                                if (xc + i < W) rowp[xc + i] = acc[p][i];
+                        }
+                    }
+                }
+            }
+        };
+
+        // The window of a group of P output rows is the N-1 rows kept from the previous group
+        // (`keep`) followed by P newly loaded rows.  PREFETCH: two buffers of new rows alternate
+        // and the next group's rows are requested before the current group is evaluated, so
+        // their latency hides behind the arithmetic inside the wave; the march is unrolled by
+        // two so the buffer in use is known at compile time and no row is copied except the
+        // N-1 kept ones.  Without PREFETCH rows are loaded just before use and other waves
+        // hide the latency.
+        constexpr int KEEP = N - 1;
+        T keep[KEEP > 0 ? KEEP : 1][V];
+        T fresh[PREFETCH ? 2 : 1][P][V];
+#pragma unroll
+        for (int k = 0; k < KEEP; ++k) load_row(y0 - a.ay + k, keep[k]);
+        if constexpr (PREFETCH) {
+#pragma unroll
+            for (int k = 0; k < P; ++k) load_row(y0 - a.ay + KEEP + k, fresh[0][k]);
         }
+
+        for (int yb = y0; yb < y1; yb += 2 * P) {
+            static_for<2>([&](auto half) __attribute__((always_inline)) {
+                constexpr int cur = PREFETCH ? decltype(half)::value : 0;
+                const int y = yb + decltype(half)::value * P;
+                if (y < y1) {
+                    if constexpr (PREFETCH) {
+                        if (y + P < y1) {
 #pragma unroll
-        for (int k = 0; k < N - 1; ++k)
+                            for (int k = 0; k < P; ++k) load_row(y + P - a.ay + KEEP + k, fresh[cur ^ 1][k]);
+                        }
+                    } else {
 #pragma unroll
-            for (int i = 0; i < V; ++i) r[k][i] = r[k + P][i];
-    }
+                        for (int k = 0; k < P; ++k) load_row(y - a.ay + KEEP + k, fresh[0][k]);
+                    }
+
+                    T acc[P][V];
+                    systolic_rows<T, V, P, Mask, false>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, wts, acc, acc);
+                    store_rows(y, acc);
+
+                    // rows P .. P+KEEP-1 of this window open the next one
+#pragma unroll
+                    for (int k = 0; k < KEEP; ++k)
+#pragma unroll
+                        for (int i = 0; i < V; ++i)
+                            keep[k][i] = (k + P < KEEP) ? keep[(k + P < KEEP) ? k + P : 0][i]
+                                                        : fresh[cur][(k + P >= KEEP) ? k + P - KEEP : 0][i];
+                }
+            });
+        }
+    };
+
+    // the mode is wave-uniform and fixed for the whole march, so no load sits behind a branch
+    if (interior) march(std::integral_constant<int, 0>{});
+    else if (vec_ok) march(std::integral_constant<int, 1>{});
+    else march(std::integral_constant<int, 2>{});
 }
 
 template <typename T, int V, int P, class Mask, bool PREFETCH, int NT>

@@ -42,15 +42,15 @@ struct PlaneStep {
         constexpr int NZ = 2 * RZ + 1;
         typedef SliceMask<RX, RY, RZ, BUDGET, RZ - K> Mask;
         if constexpr (K == NZ - 1) {
-            systolic_rows<T, V, P, Mask, false, P + 2 * RY>(r, w, acc[K], acc[K]);
+            systolic_rows<T, V, P, Mask, false>(RowBlock<T, V, P + 2 * RY>{r}, w, acc[K], acc[K]);
         } else {
-            systolic_rows<T, V, P, Mask, true, P + 2 * RY>(r, w, acc[K + 1], acc[K]);
+            systolic_rows<T, V, P, Mask, true>(RowBlock<T, V, P + 2 * RY>{r}, w, acc[K + 1], acc[K]);
             PlaneStep<T, V, P, RX, RY, RZ, BUDGET, K + 1>::run(r, w, acc);
         }
     }
 };
 
-template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT>
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT, bool PREFETCH>
 __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     const Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> a)
 {
@@ -75,91 +75,126 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     const int z0 = ztile * a.planes_per_wave;
     const int z1 = min(z0 + a.planes_per_wave, D);
     const bool vec_ok = a.aligned && (W % V) == 0;
-    const bool fast_x = vec_ok && xw0 >= 0 && xw0 + kWave * V <= W;
+    // lanes past the right halo hold nothing any stored output depends on: they re-read the last
+    // needed lane's columns (same cache line, no extra traffic, no divergence)
+    const int used_lanes = min(a.valid_lanes + 2 * HL, kWave);
+    const int xl = xw0 + min(lane, used_lanes - 1) * V;
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
     typedef Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
     const size_t plane = (size_t)W * H;
-
-    auto load_plane = [&](int z, T (&dst)[C][V]) __attribute__((always_inline)) {
-        bool zero_plane = false;
-        if (clamp) z = min(max(z, 0), D - 1);
-        else zero_plane = (z < 0 || z >= D);
-#pragma unroll
-        for (int k = 0; k < C; ++k) {
-            int y = y0 - RY + k;
-            bool zero_row = zero_plane;
-            if (clamp) y = min(max(y, 0), H - 1);
-            else zero_row = zero_row || (y < 0 || y >= H);
-            if (zero_row) {
-#pragma unroll
-                for (int i = 0; i < V; ++i) dst[k][i] = T(0);
-                continue;
-            }
-            const T* rowp = in + (size_t)z * plane + (size_t)y * W;
-            if (fast_x) {
-                load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xc, dst[k]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < V; ++i) {
-                    const int x = xc + i;
-                    if (clamp) dst[k][i] = rowp[min(max(x, 0), W - 1)];
-                    else dst[k][i] = (x >= 0 && x < W) ? rowp[x] : T(0);
-                }
-            }
-        }
-    };
-
-    T acc[NZ][P][V];
-#pragma unroll
-    for (int s = 0; s < NZ; ++s)
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[s][p][j] = T(0);
-
-    // Two plane buffers alternate: the next plane is requested before the current one is
-    // used, so its latency hides behind the arithmetic.  The march is unrolled by two so the
-    // buffer in use is known at compile time.
-    T buf[2][C][V];
-    const int nt = (z1 - z0) + 2 * RZ;    // input planes z0-RZ .. z1-1+RZ
-    load_plane(z0 - RZ, buf[0]);
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
+    const unsigned left_mask = xc < 0 ? ~0u : 0u, right_mask = xc >= W ? ~0u : 0u;
+    const unsigned left_pick = clamp ? left_mask : 0u, right_pick = clamp ? right_mask : 0u;
+    const unsigned keep_cols = clamp ? ~0u : ~(left_mask | right_mask);
+    const unsigned keep_rows = clamp ? ~0u : 0u;
+    const int nt = (z1 - z0) + 2 * RZ;    // input planes z0-RZ .. z1-1+RZ
 
-    for (int tb = 0; tb < nt; tb += 2) {
-        static_for<2>([&](auto uc) __attribute__((always_inline)) {
-            constexpr int cur = decltype(uc)::value;
-            const int t = tb + cur;
-            if (t < nt) {
-                const int zin = z0 - RZ + t;
-                if (t + 1 < nt) load_plane(zin + 1, buf[cur ^ 1]);
-                PlaneStep<T, V, P, RX, RY, RZ, BUDGET, 0>::run(buf[cur], wts, acc);
+    // "Interior" tiles touch nothing outside the grid and use aligned vectors: no checks at all.
+    // All other tiles take the general path: wave-uniform row/plane logic and per-lane selects
+    // for the columns (still vector loads when rows are V-aligned), element loads otherwise.
+    const bool interior = vec_ok && xw0 >= 0 && xw0 + used_lanes * V <= W && y0 - RY >= 0 &&
+                          y0 + P - 1 + RY < H && z0 - RZ >= 0 && z1 - 1 + RZ < D;
 
-                // output plane zin - RZ has now received its last contribution
-                const int zo = zin - RZ;
-                if (zo >= z0 && lane_stores) {
+    auto march = [&](auto mode_tag) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode_tag)::value;   // 0 interior, 1 general with vectors, 2 general by element
+        constexpr bool EDGE = MODE != 0;
+        constexpr bool VEC = MODE != 2;
+
+        auto load_plane = [&](int z, T (&dst)[C][V]) __attribute__((always_inline)) {
+            if constexpr (!EDGE) {
+                const T* pz = in + (size_t)z * plane + (size_t)(y0 - RY) * W + xl;
 #pragma unroll
-                    for (int p = 0; p < P; ++p) {
-                        const int y = y0 + p;
-                        if (y < H) {
-                            T* rowp = a.out + (size_t)zo * plane + (size_t)y * W;
-                            if (vec_ok) {
-                                store_vec<T, V, (NT & kStreamStores) != 0>(rowp + xc, acc[0][p]);
-                            } else {
+                for (int k = 0; k < C; ++k) load_vec<T, V, (NT & kStreamLoads) != 0>(pz + (size_t)k * W, dst[k]);
+            } else {
+                const bool plane_in = z >= 0 && z < D;
+                const T* pz = in + (size_t)min(max(z, 0), D - 1) * plane;
+                const int xv = min(max(xl, 0), W - V);
 #pragma unroll
-                                for (int i = 0; i < V; ++i)
-                                    if (xc + i < W) rowp[xc + i] = acc[0][p][i];
-                            }
+                for (int k = 0; k < C; ++k) {
+                    const int y = y0 - RY + k;
+                    const bool row_in = plane_in && y >= 0 && y < H;     // wave-uniform
+                    const T* rowp = pz + (size_t)min(max(y, 0), H - 1) * W;
+                    if constexpr (VEC) {
+                        // W and xc are multiples of V: a lane's V columns are all in or all out
+                        load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xv, dst[k]);
+                        const T first = dst[k][0], last = dst[k][V - 1];
+                        const unsigned keep = keep_cols & (row_in ? ~0u : keep_rows);
+#pragma unroll
+                        for (int i = 0; i < V; ++i)
+                            dst[k][i] = keep_if(pick(pick(dst[k][i], first, left_pick), last, right_pick), keep);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) {
+                            const int x = xc + i;
+                            const T v = rowp[min(max(x, 0), W - 1)];
+                            dst[k][i] = (clamp || (row_in && x >= 0 && x < W)) ? v : T(0);
                         }
                     }
                 }
             }
-        });
-    }
+        };
+
+        T acc[NZ][P][V];
+#pragma unroll
+        for (int s = 0; s < NZ; ++s)
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[s][p][j] = T(0);
+
+        // Two plane buffers alternate: the next plane is requested before the current one is
+        // used, so its latency hides behind the arithmetic.  The march is unrolled by two so the
+        // buffer in use is known at compile time.
+        T buf[PREFETCH ? 2 : 1][C][V];
+        if constexpr (PREFETCH) load_plane(z0 - RZ, buf[0]);
+
+        for (int tb = 0; tb < nt; tb += 2) {
+            static_for<2>([&](auto uc) __attribute__((always_inline)) {
+                constexpr int cur = PREFETCH ? decltype(uc)::value : 0;
+                const int t = tb + decltype(uc)::value;
+                if (t < nt) {
+                    const int zin = z0 - RZ + t;
+                    if constexpr (PREFETCH) {
+                        if (t + 1 < nt) load_plane(zin + 1, buf[cur ^ 1]);
+                    } else {
+                        load_plane(zin, buf[0]);   // no second buffer: other waves hide the latency
+                    }
+                    PlaneStep<T, V, P, RX, RY, RZ, BUDGET, 0>::run(buf[cur], wts, acc);
+
+                    // output plane zin - RZ has now received its last contribution
+                    const int zo = zin - RZ;
+                    if (zo >= z0 && lane_stores) {
+                        T* po = a.out + (size_t)zo * plane + (size_t)y0 * W + xc;
+#pragma unroll
+                        for (int p = 0; p < P; ++p) {
+                            T* rowp = po + (size_t)p * W;
+                            if constexpr (!EDGE) {
+                                store_vec<T, V, (NT & kStreamStores) != 0>(rowp, acc[0][p]);
+                            } else if (y0 + p < H) {
+                                if constexpr (VEC) {
+                                    store_vec<T, V, (NT & kStreamStores) != 0>(rowp, acc[0][p]);
+                                } else {
+#pragma unroll
+                                    for (int i = 0; i < V; ++i)
+                                        if (xc + i < W) rowp[i] = acc[0][p][i];
+                                }
+                            }
+                        }
+                    }
+                }
+            });
+        }
+    };
+
+    // the mode is wave-uniform and fixed for the whole march, so no load sits behind a branch
+    if (interior) march(std::integral_constant<int, 0>{});
+    else if (vec_ok) march(std::integral_constant<int, 1>{});
+    else march(std::integral_constant<int, 2>{});
 }
 
-template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT>
+template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT, bool PREFETCH>
 hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
@@ -205,15 +240,15 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
                 else idx = (k * NX + m) * NY + n;
                 a.w[idx] = c[(k * NY + n) * NX + m];
             }
-    hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET, NT>), dim3(g.blocks), dim3(kBlock), 0,
+    hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET, NT, PREFETCH>), dim3(g.blocks), dim3(kBlock), 0,
                        pr.stream, a);
     return hipGetLastError();
 }
 
-#define SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, NT, VARIANT)                              \
+#define SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, PREFETCH, NT, VARIANT)                    \
     static ::ssam::Register3D SSAM_CAT(reg3d_, __COUNTER__)(::ssam::Instance3D{                      \
-        #T "_r" #RX #RY #RZ "_b" #BUDGET "_v" #V "p" #P "nt" #NT, DT, RX, RY, RZ, BUDGET, VARIANT,    \
-        &::ssam::launch3d<T, V, P, RX, RY, RZ, BUDGET, NT>})
-#define SSAM_INSTANCE_3D(T, DT, V, P, RX, RY, RZ, BUDGET) SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, 2, 0)
+        #T "_r" #RX #RY #RZ "_b" #BUDGET "_v" #V "p" #P "f" #PREFETCH "nt" #NT, DT, RX, RY, RZ,       \
+        BUDGET, VARIANT, &::ssam::launch3d<T, V, P, RX, RY, RZ, BUDGET, NT, (PREFETCH) != 0>})
+#define SSAM_INSTANCE_3D(T, DT, V, P, RX, RY, RZ, BUDGET) SSAM_INSTANCE_3D_V(T, DT, V, P, RX, RY, RZ, BUDGET, 1, 2, 0)
 
 }  // namespace ssam
