@@ -36,3 +36,31 @@ def expanded_window(full_shape: Sequence[int], lo: Sequence[int], hi: Sequence[i
     elo = tuple(max(0, l - r) for l, r in zip(lo, reach_lo))
     ehi = tuple(min(n, h + r) for n, h, r in zip(full_shape, hi, reach_hi))
     return elo, ehi
+
+
+def reach_of(case):
+    """Per-axis dependency reach (low side, high side) of the whole run, slowest axis first."""
+    if case.kind == "conv2d":
+        N, M = case.coef.shape
+        ax, ay = M // 2, N // 2
+        return (ay, ax), (N - 1 - ay, M - 1 - ax)
+    r = [s // 2 * case.steps for s in case.coef.shape]
+    if case.kind == "stencil2d":
+        r = r[1:]
+    return tuple(r), tuple(r)
+
+
+def oracle_window(case, lo, hi):
+    rlo, rhi = reach_of(case)
+    elo, ehi = expanded_window(case.shape, lo, hi, rlo, rhi)
+    crop = case.window(elo, tuple(h - l for l, h in zip(elo, ehi)))
+    import oracle
+    if case.kind == "conv2d":
+        full = oracle.conv2d(crop, case.coef, case.boundary)
+    else:
+        coef = case.coef if case.kind == "stencil3d" else case.coef[0]
+        full = oracle.iterate(crop, coef, case.steps, case.boundary)
+    sl = tuple(slice(l - e, h - e) for l, h, e in zip(lo, hi, elo))
+    return full[sl]
+
+

@@ -373,3 +373,30 @@ def test_zero_coefficient_means_no_tap():
     out = oracle.stencil(fld, coef, "zero")
     assert out[2, 2] == 4.0
     assert np.isinf(out[2, 1])
+
+
+# ---------------------------------------------------------------------------------------
+# 6. The windowed evaluation used by the full-size GPU parity tests equals the full-grid oracle.
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kind", ["conv2d", "stencil2d", "stencil3d"])
+def test_windowed_oracle_equals_full_grid_oracle(kind):
+    from parity_util import oracle_window
+    if kind == "conv2d":
+        case = wl.Case("w_conv", "conv2d", np.float32, (40, 50), (0.0, 1.0), 3, wl.seeded_filter(5, 4, 9, np.float32),
+                       "clamp", 1)
+        full = oracle.conv2d(case.field(), case.coef, "clamp")
+        wins = [((0, 0), (6, 7)), ((34, 43), (40, 50)), ((15, 20), (22, 31)), ((0, 30), (3, 50))]
+    elif kind == "stencil2d":
+        case = wl.Case("w_s2", "stencil2d", np.float64, (40, 50), (-1.0, 1.0), 5,
+                       wl.seeded_coefficients(wl.mask_star(2, 2), 8, np.float64), "zero", 4)
+        full = oracle.iterate(case.field(), case.coef[0], 4, "zero")
+        wins = [((0, 0), (6, 7)), ((34, 43), (40, 50)), ((15, 20), (22, 31))]
+    else:
+        case = wl.Case("w_s3", "stencil3d", np.float64, (14, 15, 16), (-1.0, 1.0), 6,
+                       wl.seeded_coefficients(wl.mask_box(1, 1, 1), 7, np.float64), "zero", 3)
+        full = oracle.iterate(case.field(), case.coef, 3, "zero")
+        wins = [((0, 0, 0), (4, 4, 4)), ((10, 11, 12), (14, 15, 16)), ((5, 5, 5), (9, 8, 10))]
+    for lo, hi in wins:
+        sl = tuple(slice(l, h) for l, h in zip(lo, hi))
+        assert np.array_equal(oracle_window(case, lo, hi), full[sl])
