@@ -93,16 +93,24 @@ inline bool pointers_aligned(const void* a, const void* b, size_t bytes)
 }
 
 // Overlapped blocking along x (paper Sec. 4.5 / 4.7 re-derived for 64 lanes of V columns):
-// a wave caches 64*V columns and stores valid_lanes*V of them.  Strips are balanced so the
-// last one is not mostly empty.
+// a wave caches 64*V columns and stores valid_lanes*V of them.  The strip width is kept a
+// multiple of 8 lanes = 128 bytes where possible, so that strips start on cache-line
+// boundaries and no line is written by two waves (measured: +7 % on 8192^2); among such
+// widths the smallest that still covers W with the same number of strips is taken, so the
+// last strip is not mostly empty.
 inline void plan_strips(int W, int V, int halo_left, int halo_right, int valid_override, Geometry* g)
 {
     const int vmax = 64 - halo_left - halo_right;
-    int valid = vmax;
-    if (valid_override > 0 && valid_override < vmax) valid = valid_override;
-    int strips = ceil_div(W, valid * V);
-    if (valid_override <= 0) valid = ceil_div(ceil_div(W, strips), V);  // balance
-    if (valid > vmax) valid = vmax;
+    int valid;
+    if (valid_override > 0) {
+        valid = valid_override < vmax ? valid_override : vmax;
+    } else {
+        const int vline = vmax >= 8 ? vmax / 8 * 8 : vmax;   // widest line-aligned strip
+        const int strips = ceil_div(W, vline * V);
+        valid = ceil_div(ceil_div(W, strips), V);             // balanced
+        if (vmax >= 8) valid = ceil_div(valid, 8) * 8;
+        if (valid > vline) valid = vline;
+    }
     g->V = V;
     g->halo_left = halo_left;
     g->halo_right = halo_right;
