@@ -25,9 +25,10 @@ enum : int { kZero = 0, kClamp = 1 };
 // ---- whole-wave shift by one lane ------------------------------------------------------
 // shift_up:   lane L receives the value lane L-1 held (lane 0 receives 0).
 // shift_down: lane L receives the value lane L+1 held (lane 63 receives 0).
-// DPP control 0x138 = wave_shr:1, 0x130 = wave_shl:1 (GFX9 encoding).
-__device__ __forceinline__ int dpp_up(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xf, 0xf, false); }
-__device__ __forceinline__ int dpp_down(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x130, 0xf, 0xf, false); }
+// DPP control 0x138 = wave_shr:1, 0x130 = wave_shl:1 (GFX9 encoding).  bound_ctrl makes the
+// lane without a source read 0, so no "old" value has to be materialised first.
+__device__ __forceinline__ int dpp_up(int v) { return __builtin_amdgcn_mov_dpp(v, 0x138, 0xf, 0xf, true); }
+__device__ __forceinline__ int dpp_down(int v) { return __builtin_amdgcn_mov_dpp(v, 0x130, 0xf, 0xf, true); }
 
 __device__ __forceinline__ float shift_up(float v) { return __builtin_bit_cast(float, dpp_up(__builtin_bit_cast(int, v))); }
 __device__ __forceinline__ float shift_down(float v) { return __builtin_bit_cast(float, dpp_down(__builtin_bit_cast(int, v))); }
@@ -50,6 +51,23 @@ __device__ __forceinline__ double shift_down(double v)
 
 __device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 __device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+// x * c + addend written as a three-address FMA (c wave-uniform, in scalar registers).  The
+// compiler prefers the two-address form, which overwrites the addend's register; when the
+// result has to live in a *different* register than the addend (the in-flight planes of the 3D
+// march advance one slot per step) that costs a move per value, which this form avoids.
+__device__ __forceinline__ float fma_into(float x, float c, float addend)
+{
+    float d;
+    asm("v_fma_f32 %0, %1, %2, %3" : "=v"(d) : "s"(c), "v"(x), "v"(addend));
+    return d;
+}
+__device__ __forceinline__ double fma_into(double x, double c, double addend)
+{
+    double d;
+    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(d) : "s"(c), "v"(x), "v"(addend));
+    return d;
+}
 
 // ---- coefficients -------------------------------------------------------------------------
 // Coefficients live in the kernel-argument block and are read through a constant-address-space
@@ -225,14 +243,14 @@ struct RowPair {                // HEAD rows kept from the previous window, then
 // Products of one filter column, for all P window positions: the lane's own column i = j + COL
 // multiplies filter column AX + DX and accumulates into the partial sum of output column j.
 // (Sec. 4.3: an N-term inner product between a register vector and a filter column.)
-template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, class Rows>
+template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, bool SKIP_ANCHOR, class Rows>
 __device__ __forceinline__ void column_products(const Rows& r, ConstPtr<T> w, T (&s)[P][V])
 {
     constexpr int N = Mask::kN, AX = Mask::kAX;
     const int z = PIN ? opaque_zero() : 0;
 #pragma unroll
     for (int n = 0; n < N; ++n) {
-        if (Mask::tap(n, AX + DX)) {
+        if (Mask::tap(n, AX + DX) && !(SKIP_ANCHOR && DX == 0 && n == Mask::kAY)) {
             const T wv = w[Mask::widx(n, AX + DX) + z];
 #pragma unroll
             for (int j = 0; j < V; ++j) {
@@ -291,10 +309,12 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
     T sum[P][V];
     bool have = ACCUMULATE;   // folds to a constant: does `sum` hold a value yet
     if constexpr (ACCUMULATE) {
+        // the anchor tap (every mask has it) seeds the sums from `in` with a three-address FMA
+        const T wa = w[Mask::widx(Mask::kAY, Mask::kAX)];
 #pragma unroll
         for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int j = 0; j < V; ++j) sum[p][j] = in[p][j];
+            for (int j = 0; j < V; ++j) sum[p][j] = fma_into(r.at(p + Mask::kAY, j), wa, in[p][j]);
     }
 
     // chain arriving from the left (lower lane ids)
@@ -310,7 +330,7 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) - d * V;
                 if constexpr (dx >= -Mask::kLeft && dx <= -1)
-                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, Rows>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, false, Rows>(r, w, s);
             });
 #pragma unroll
             for (int p = 0; p < P; ++p)
@@ -339,7 +359,7 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) + d * V;
                 if constexpr (dx >= 1 && dx <= Mask::kRight)
-                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, Rows>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, false, Rows>(r, w, s);
             });
 #pragma unroll
             for (int p = 0; p < P; ++p)
@@ -366,7 +386,7 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
     static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
         constexpr int dx = decltype(cc)::value - (V - 1);
         if constexpr (dx >= -Mask::kLeft && dx <= Mask::kRight)
-            column_products<T, V, P, Mask, dx, dx, PIN, Rows>(r, w, sum);
+            column_products<T, V, P, Mask, dx, dx, PIN, ACCUMULATE, Rows>(r, w, sum);
     });
 #pragma unroll
     for (int p = 0; p < P; ++p)
