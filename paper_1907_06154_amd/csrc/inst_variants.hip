@@ -9,10 +9,6 @@ SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 1, 2, 2);
 SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 3, 1, 2, 0, 2, 3);
 SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 0, 2, 1);
 SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 1, 1, 1, 3, 1, 2, 1);
-SSAM_INSTANCE_3D_V(double, SSAM_F64, 2, 4, 4, 4, 4, 1, 1, 2, 1);
-SSAM_INSTANCE_3D_V(float, SSAM_F32, 4, 4, 4, 4, 4, 1, 0, 2, 1);
-SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 4, 4, 4, 1, 0, 2, 2);
-SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 8, 4, 4, 4, 1, 0, 2, 3);
 SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 1, 1, 1, 1, 1, 2, 1);
 SSAM_INSTANCE_3D_V(float, SSAM_F32, 2, 4, 1, 1, 1, 3, 1, 2, 1);
 SSAM_INSTANCE_3D_V(float, SSAM_F32, 4, 4, 1, 1, 1, 1, 0, 2, 2);

@@ -196,12 +196,45 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     else march(std::integral_constant<int, 2>{});
 }
 
+// Fills the kernel-argument block: pointers, sizes, tile plan and the packed coefficients.
+template <typename T, int V, int RX, int RY, int RZ, int BUDGET>
+void fill_args3d(const Problem3D& pr, const Geometry& g, Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW>* a)
+{
+    typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
+    constexpr int NX = 2 * RX + 1, NY = 2 * RY + 1, NZ = 2 * RZ + 1;
+    a->in = static_cast<const T*>(pr.in);
+    a->out = static_cast<T*>(pr.out);
+    a->W = pr.W;
+    a->H = pr.H;
+    a->D = pr.D;
+    a->boundary = pr.boundary;
+    a->strips_x = g.strips_x;
+    a->tiles_y = g.tiles_y;
+    a->tiles = g.tiles;
+    a->valid_lanes = g.valid_lanes;
+    a->planes_per_wave = g.planes_per_wave;
+    a->blocks = g.blocks;
+    a->xcd_remap = g.xcd_remap;
+    a->aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
+    const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
+    for (int i = 0; i < Mask0::kNW; ++i) a->w[i] = T(0);
+    for (int k = 0; k < NZ; ++k)
+        for (int n = 0; n < NY; ++n)
+            for (int m = 0; m < NX; ++m) {
+                const int used = (k != RZ) + (n != RY) + (m != RX);
+                if (used > BUDGET) continue;
+                int idx;
+                if (BUDGET == 1) idx = k != RZ ? k : (n != RY ? NZ + n : (m != RX ? NZ + NY + m : RZ));
+                else idx = (k * NX + m) * NY + n;
+                a->w[idx] = c[(k * NY + n) * NX + m];
+            }
+}
+
 template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT, bool PREFETCH>
 hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
     constexpr int HL = (RX + V - 1) / V;
-    constexpr int NX = 2 * RX + 1, NY = 2 * RY + 1, NZ = 2 * RZ + 1;
     Geometry g;
     plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g);
     g.P = P;
@@ -216,32 +249,7 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     if (dry_run) return hipSuccess;
 
     Args3D<T, Mask0::kNW> a;
-    a.in = static_cast<const T*>(pr.in);
-    a.out = static_cast<T*>(pr.out);
-    a.W = pr.W;
-    a.H = pr.H;
-    a.D = pr.D;
-    a.boundary = pr.boundary;
-    a.strips_x = g.strips_x;
-    a.tiles_y = g.tiles_y;
-    a.tiles = g.tiles;
-    a.valid_lanes = g.valid_lanes;
-    a.planes_per_wave = g.planes_per_wave;
-    a.blocks = g.blocks;
-    a.xcd_remap = g.xcd_remap;
-    a.aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
-    const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
-    for (int i = 0; i < Mask0::kNW; ++i) a.w[i] = T(0);
-    for (int k = 0; k < NZ; ++k)
-        for (int n = 0; n < NY; ++n)
-            for (int m = 0; m < NX; ++m) {
-                const int used = (k != RZ) + (n != RY) + (m != RX);
-                if (used > BUDGET) continue;
-                int idx;
-                if (BUDGET == 1) idx = k != RZ ? k : (n != RY ? NZ + n : (m != RX ? NZ + NY + m : RZ));
-                else idx = (k * NX + m) * NY + n;
-                a.w[idx] = c[(k * NY + n) * NX + m];
-            }
+    fill_args3d<T, V, RX, RY, RZ, BUDGET>(pr, g, &a);
     hipLaunchKernelGGL((ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET, NT, PREFETCH>), dim3(g.blocks), dim3(kBlock), 0,
                        pr.stream, a);
     return hipGetLastError();

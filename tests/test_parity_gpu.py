@@ -21,7 +21,7 @@ def ssam():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     s.lib()   # raises if the HIP library is missing: there is no fallback
     yield s
-    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic"):
+    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant"):
         s.ssam_set_tuning(name, -1)
 
 
@@ -125,6 +125,8 @@ def test_stencil3d(ssam, dtype, kind, r, boundary):
 @pytest.mark.parametrize("tuning", [
     {"rows_per_wave": 8}, {"valid_lanes": 17}, {"xcd_remap": 0}, {"planes_per_wave": 5},
     {"rows_per_wave": 16, "valid_lanes": 40, "planes_per_wave": 3, "xcd_remap": 0}, {"force_generic": 1},
+    {"variant": 1}, {"variant": 2}, {"variant": 3}, {"variant": 7}, {"variant": 8},
+    {"variant": 7, "planes_per_wave": 5, "valid_lanes": 24}, {"variant": 8, "planes_per_wave": 2, "xcd_remap": 0},
 ])
 def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
     try:
@@ -137,10 +139,14 @@ def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
         fld = wl.uniform_field((70, 300), -1.0, 1.0, 703, np.float64)
         c2 = stencil2d_coef("star", 4, np.float64, 704)
         assert_parity(host(ssam.ssam_stencil2d(dev(fld), c2, "zero")), oracle.stencil(fld, c2, "zero"), c2, 1.0)
-        f3 = wl.uniform_field((20, 13, 259), -1.0, 1.0, 705, np.float64)
-        for kind, r in (("box", 1), ("star", 4)):
-            c3 = stencil3d_coef(kind, r, np.float64, 706)
-            assert_parity(host(ssam.ssam_stencil3d(dev(f3), c3, "clamp")), oracle.stencil(f3, c3, "clamp"), c3, 1.0)
+        for dt in (np.float64, np.float32):
+            for shape in ((20, 13, 259), (9, 37, 260)):
+                f3 = wl.uniform_field(shape, -1.0, 1.0, 705, dt)
+                for kind, r in (("box", 1), ("star", 1), ("star", 4)):
+                    c3 = stencil3d_coef(kind, r, dt, 706)
+                    for bnd in ("clamp", "zero"):
+                        assert_parity(host(ssam.ssam_stencil3d(dev(f3), c3, bnd)), oracle.stencil(f3, c3, bnd), c3, 1.0,
+                                      f"{tuning} {kind} r{r} {bnd} {shape}")
     finally:
         for k in tuning:
             ssam.ssam_set_tuning(k, -1)
