@@ -98,17 +98,18 @@ inline bool pointers_aligned(const void* a, const void* b, size_t bytes)
 // boundaries and no line is written by two waves (measured: +7 % on 8192^2); among such
 // widths the smallest that still covers W with the same number of strips is taken, so the
 // last strip is not mostly empty.
-inline void plan_strips(int W, int V, int halo_left, int halo_right, int valid_override, Geometry* g)
+inline void plan_strips(int W, int V, int halo_left, int halo_right, int valid_override, Geometry* g,
+                        bool line_aligned = true)
 {
     const int vmax = 64 - halo_left - halo_right;
     int valid;
     if (valid_override > 0) {
         valid = valid_override < vmax ? valid_override : vmax;
     } else {
-        const int vline = vmax >= 8 ? vmax / 8 * 8 : vmax;   // widest line-aligned strip
+        const int vline = (line_aligned && vmax >= 8) ? vmax / 8 * 8 : vmax;   // widest (line-aligned) strip
         const int strips = ceil_div(W, vline * V);
         valid = ceil_div(ceil_div(W, strips), V);             // balanced
-        if (vmax >= 8) valid = ceil_div(valid, 8) * 8;
+        if (line_aligned && vmax >= 8) valid = ceil_div(valid, 8) * 8;
         if (valid > vline) valid = vline;
     }
     g->V = V;
@@ -116,6 +117,43 @@ inline void plan_strips(int W, int V, int halo_left, int halo_right, int valid_o
     g->halo_right = halo_right;
     g->valid_lanes = valid;
     g->strips_x = ceil_div(W, valid * V);
+}
+
+// Waves of `kernel` (launched as blocks of 4 waves) the whole device can hold at once.  Falls
+// back to a typical figure when no device is present (planning queries on a CPU-only host).
+inline int wave_slots(const void* kernel)
+{
+    int blocks_per_cu = 0, dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, kernel, 256, 0) != hipSuccess ||
+        blocks_per_cu <= 0) {
+        (void)hipGetLastError();
+        return 256 * 3 * 4;
+    }
+    return cus * blocks_per_cu * 4;
+}
+
+// Rows per tile (a multiple of P, at least min_rows) such that strips * ceil(H / rows) tiles fill
+// `slots` wave slots k times as exactly as possible, for the smallest k that allows it.
+inline int balanced_rows(int H, int P, int strips, int slots, int min_rows)
+{
+    int best_rows = ceil_div(H, P) * P;
+    double best_eff = 0.0;
+    for (int k = 1; k <= 4; ++k) {
+        const int ytiles = slots * k / strips;
+        if (ytiles < 1) continue;
+        int rows = ceil_div(ceil_div(H, ytiles), P) * P;
+        if (rows < min_rows) rows = ceil_div(min_rows, P) * P;
+        const long tiles = (long)strips * ceil_div(H, rows);
+        const long rounds = (tiles + slots - 1) / slots;
+        const double eff = (double)tiles / ((double)rounds * slots);
+        if (eff > best_eff + 0.02) {
+            best_eff = eff;
+            best_rows = rows;
+        }
+    }
+    return best_rows;
 }
 
 inline void plan_blocks(Geometry* g, int remap_override)

@@ -190,9 +190,21 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     constexpr int M = Mask::kM, N = Mask::kN;
     constexpr int HL = (Mask::kLeft + V - 1) / V, HR = (Mask::kRight + V - 1) / V;
     Geometry g;
-    plan_strips(pr.W, V, HL, HR, tu.valid_lanes, &g);
+    // arithmetic-bound filters use every lane they can; bandwidth-bound ones keep strips line-aligned
+    plan_strips(pr.W, V, HL, HR, tu.valid_lanes, &g, Mask::kNW < 64);
     g.P = P;
-    int rows = tu.rows_per_wave > 0 ? tu.rows_per_wave : (N <= 5 ? 32 : (N <= 11 ? 64 : 128));
+    int rows;
+    if (tu.rows_per_wave > 0) {
+        rows = tu.rows_per_wave;
+    } else if (Mask::kNW >= 64) {
+        // arithmetic-heavy filters: every wave takes about the same time, so the tile count should
+        // fill the machine's wave slots a whole number of times (a partly filled last round costs
+        // a full one).  Measured on 8192^2, 20x20: 57 -> 73 GStencil/s.
+        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_kernel<T, V, P, Mask, PREFETCH, NT>));
+        rows = balanced_rows(pr.H, P, g.strips_x, slots, 3 * (N - 1));
+    } else {
+        rows = N <= 5 ? 32 : 64;   // bandwidth-bound: short tiles measured best
+    }
     rows = ceil_div(rows, P) * P;
     if (rows > ceil_div(pr.H, P) * P) rows = ceil_div(pr.H, P) * P;
     g.rows_per_wave = rows;
