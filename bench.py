@@ -31,9 +31,27 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0                          # MI355X HBM3E, published
 ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}   # published vector peaks (fp32 figure assumes packed FMA)
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
-# same counters' reading for ssam_probe_copy of known size; see profiles/.  Keyed by case name.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# factors being what the same counters read for ssam_probe_copy of known size); the runs and
+# their commands are summarised under profiles/.  Keyed by case name; offline figures, not
+# re-measured by this script.
+MEASURED_TRAFFIC_BYTES = {
+    "c2_conv3x3_f32": 554059143,
+    "c2_conv5x5_f32": 565128212,
+    "c2_conv9x9_f32": 571815793,
+    "c2_conv15x15_f32": 590394654,
+    "c2_conv20x20_f32": 600009449,
+    "c2_conv3x11_f32": 582322822,
+    "c2_conv11x3_f32": 551139449,
+    "c3_2d_box_r1_f64": 1102485294,
+    "c3_2d_box_r2_f64": 1083534618,
+    "c3_2d_star_r4_f64": 1129549854,
+    "c4_3d_star_r1_f64": 2436739858,
+    "c4_3d_box_r1_f64": 2379723841,
+    "c4_3d_faces_edges_f64": 2382340545,
+    "c5_3d_star_r4_f32": 1248362483,
+    "c5_3d_star_r4_f64": 2444633941,
+}
 
 
 def dtype_tag(dt) -> str:
@@ -57,30 +75,41 @@ def run_case(ssam, case, bufs):
         ssam.ssam_stencil_iterate(a, b, case_coef(case), case.steps, case.boundary)
 
 
-def cpu_baseline(cases, budget_taps: float):
+def cpu_baseline(cases, target_seconds: float):
     """Times the oracle, as it stands, on a bounded sample: the leading rows (planes) of each
-    case's grid, one sweep each, sized so that the whole sample costs about `budget_taps`
-    multiply-adds.  Returns GStencil/s over the sample."""
+    case's grid, one sweep each.  A short calibration run measures the oracle's rate on this
+    host, then the sample is sized for about `target_seconds` of oracle time in total.
+    Returns GStencil/s over the sample."""
     import oracle
     from paper_1907_06154_amd import workloads as wl
-    pts = 0
-    secs = 0.0
-    desc = []
-    for case in cases:
-        shape = list(case.shape)
-        inner = int(np.prod(shape[1:]))
-        want_pts = budget_taps / len(cases) / max(1, case.taps)
-        shape[0] = max(1, min(shape[0], int(want_pts // inner)))
+
+    def run(case, lead):
+        shape = (lead,) + tuple(case.shape[1:])
         # the leading block of the row-major field is a prefix of the same counter stream
-        sample = wl.uniform_field(tuple(shape), case.field_range[0], case.field_range[1], case.field_seed, case.dtype)
+        sample = wl.uniform_field(shape, case.field_range[0], case.field_range[1], case.field_seed, case.dtype)
         t0 = time.perf_counter()
         if case.kind == "conv2d":
             oracle.conv2d(sample, case.coef, case.boundary)
         else:
             oracle.stencil(sample, case_coef(case), case.boundary)
-        secs += time.perf_counter() - t0
-        pts += int(np.prod(shape))
-        desc.append("x".join(str(s) for s in shape))
+        return time.perf_counter() - t0, int(np.prod(shape))
+
+    # calibration: about 2e8 multiply-adds on the first case
+    c0 = cases[0]
+    inner0 = int(np.prod(c0.shape[1:]))
+    lead0 = max(1, min(c0.shape[0], int(2e8 / max(1, c0.taps) / inner0)))
+    dt, n = run(c0, lead0)
+    taps_per_s = n * c0.taps / max(dt, 1e-6)
+
+    pts, secs, desc = 0, 0.0, []
+    for case in cases:
+        inner = int(np.prod(case.shape[1:]))
+        want_pts = target_seconds / len(cases) * taps_per_s / max(1, case.taps)
+        lead = max(1, min(case.shape[0], int(want_pts // inner)))
+        dt, n = run(case, lead)
+        secs += dt
+        pts += n
+        desc.append("x".join(str(v) for v in (lead,) + tuple(case.shape[1:])))
     return {"value": pts / secs / 1e9, "unit": "GStencil/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"one sweep of each of the {len(cases)} cases on the leading block of its grid "
                       f"({', '.join(desc)}; {pts} points, {secs:.1f} s of oracle time)"}
@@ -94,7 +123,7 @@ def main() -> int:
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5"])
     ap.add_argument("--cases", default=None, help="comma-separated substrings selecting cases of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-taps", type=float, default=24e9, help="oracle sample size in multiply-adds")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -233,7 +262,7 @@ def main() -> int:
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cases, args.cpu_taps)
+        out["cpu_baseline"] = cpu_baseline(cases, args.cpu_seconds)
     print(json.dumps(out))
     return 0
 

@@ -20,3 +20,12 @@ SSAM_INSTANCE_2D_V(double, SSAM_F64, 2, 4, 3, 3, 1, 2, 1, 2, 4);
 SSAM_INSTANCE_2D_V(double, SSAM_F64, 2, 8, 3, 3, 1, 2, 0, 2, 5);
 SSAM_INSTANCE_2D_V(double, SSAM_F64, 2, 4, 3, 3, 1, 2, 0, 2, 6);
 SSAM_INSTANCE_2D_V(double, SSAM_F64, 2, 16, 3, 3, 1, 2, 0, 2, 7);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 9, 9, 4, 2, 1, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 9, 9, 4, 2, 0, 2, 2);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 3, 11, 1, 2, 1, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 3, 11, 1, 2, 0, 2, 2);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 11, 3, 5, 2, 1, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 11, 3, 5, 2, 0, 2, 2);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 15, 15, 7, 2, 0, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 20, 20, 10, 2, 0, 2, 1);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 2, 20, 20, 10, 2, 1, 2, 2);
