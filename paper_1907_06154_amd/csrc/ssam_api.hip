@@ -202,10 +202,6 @@ bool overlap(const void* a, const void* b, size_t bytes)
 size_t elem(int dtype) { return dtype == SSAM_F32 ? 4 : 8; }
 
 // ---- dispatch ---------------------------------------------------------------------------
-struct Choice2D {
-    const Instance2D* inst = nullptr;
-};
-
 template <typename T>
 const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant)
 {

@@ -60,3 +60,14 @@ def test_config_catalogue():
     c1 = cfg["config1"][0]
     assert c1.coef.max() < 0.25 and c1.coef[c1.coef != 0].min() > 0
     assert cfg["config2"][0].boundary == "clamp" and cfg["config3"][0].steps == 100
+
+
+def test_oracle_and_generators_match_the_committed_lock_file():
+    """tests/golden/oracle_lock.txt is written by tests/golden/make_golden.py (oracle only)."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert mod.render() == open(os.path.join(here, "golden", "oracle_lock.txt")).read()
