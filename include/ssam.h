@@ -95,7 +95,8 @@ const char *ssam_status_string(int status);
 /* Tuning override for experiments and benchmarks (not needed for correct use): sets a named
  * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
  * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant" (an alternative
- * compiled instance of the same shape, where one exists).
+ * compiled instance of the same shape, where one exists), "march_axis" (3D: 0 = march along z,
+ * 1 = march along y).
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 

@@ -25,7 +25,7 @@ std::vector<Instance3D>& registry3d()
 namespace {
 
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
-    g_force_generic{-1}, g_variant{-1};
+    g_force_generic{-1}, g_variant{-1}, g_march_axis{-1};
 
 Tuning current_tuning()
 {
@@ -36,6 +36,7 @@ Tuning current_tuning()
     t.xcd_remap = g_xcd_remap.load();
     t.force_generic = g_force_generic.load();
     t.variant = g_variant.load();
+    t.march_axis = g_march_axis.load();
     return t;
 }
 
@@ -261,18 +262,22 @@ const Instance3D* pick3d(const Problem3D& p, int want_variant)
     const T* c = static_cast<const T*>(p.c);
     int budget = tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
     if (budget == 0) budget = 1;
+    // an instance is compiled for (reach along x, along the strip axis, along the march axis)
+    const int strip_r = p.march_y ? p.rz : p.ry, march_r = p.march_y ? p.ry : p.rz;
     const Instance3D* best = nullptr;
     for (const Instance3D& i : registry3d()) {
-        if (i.dtype != p.dtype || i.rx != p.rx || i.ry != p.ry || i.rz != p.rz || i.budget < budget) continue;
+        if (i.dtype != p.dtype || i.rx != p.rx || i.ry != strip_r || i.rz != march_r || i.budget < budget) continue;
         if (i.variant != want_variant) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
 }
 
-int run3d(const Problem3D& p, Geometry* geo, bool dry, std::string* name)
+int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
 {
     const Tuning tu = current_tuning();
+    Problem3D p = p_in;
+    p.march_y = tu.march_axis == 1;
     if (p.D == 1 && p.rz == 0) {   // a 2D problem through the 3D door
         Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
         return run2d(q, true, geo, dry, name);
@@ -429,6 +434,7 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "xcd_remap")) g_xcd_remap = value;
     else if (!strcmp(name, "force_generic")) g_force_generic = value;
     else if (!strcmp(name, "variant")) g_variant = value;
+    else if (!strcmp(name, "march_axis")) g_march_axis = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

@@ -21,6 +21,7 @@ struct Tuning {
     int xcd_remap = -1;        // 1: consecutive logical blocks share an XCD
     int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
     int variant = -1;          // pick an alternative compiled instance of the same shape
+    int march_axis = -1;       // 3D: 0 march along z (strip along y), 1 march along y (strip along z)
 };
 
 struct Problem2D {
@@ -41,6 +42,7 @@ struct Problem3D {
     int rx, ry, rz;
     int boundary, dtype;
     hipStream_t stream;
+    bool march_y = false;  // march along y with the register strip along z (instances see ry, rz exchanged)
 };
 
 // Tile geometry of one launch (all host arithmetic; also reported by ssam_describe).

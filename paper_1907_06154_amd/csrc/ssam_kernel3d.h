@@ -26,6 +26,7 @@ struct Args3D {
     int blocks;
     int xcd_remap;
     int aligned;
+    long stride_row, stride_plane;   // element strides of the strip axis and of the march axis
     T w[NW];
 };
 
@@ -85,7 +86,10 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
     const T* __restrict__ in = a.in;
     typedef Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
-    const size_t plane = (size_t)W * H;
+    // strides of the two outer axes in elements: the rows of a lane's strip are `rowst` apart, the
+    // planes the wave marches over `plane` apart (W and W*H when marching z; swapped when the host
+    // asks for a march along y, where a.H and a.D are then the extents of z and y)
+    const size_t rowst = (size_t)a.stride_row, plane = (size_t)a.stride_plane;
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
     const unsigned left_mask = xc < 0 ? ~0u : 0u, right_mask = xc >= W ? ~0u : 0u;
     const unsigned left_pick = clamp ? left_mask : 0u, right_pick = clamp ? right_mask : 0u;
@@ -106,9 +110,9 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
 
         auto load_plane = [&](int z, T (&dst)[C][V]) __attribute__((always_inline)) {
             if constexpr (!EDGE) {
-                const T* pz = in + (size_t)z * plane + (size_t)(y0 - RY) * W + xl;
+                const T* pz = in + (size_t)z * plane + (size_t)(y0 - RY) * rowst + xl;
 #pragma unroll
-                for (int k = 0; k < C; ++k) load_vec<T, V, (NT & kStreamLoads) != 0>(pz + (size_t)k * W, dst[k]);
+                for (int k = 0; k < C; ++k) load_vec<T, V, (NT & kStreamLoads) != 0>(pz + (size_t)k * rowst, dst[k]);
             } else {
                 const bool plane_in = z >= 0 && z < D;
                 const T* pz = in + (size_t)min(max(z, 0), D - 1) * plane;
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
                 for (int k = 0; k < C; ++k) {
                     const int y = y0 - RY + k;
                     const bool row_in = plane_in && y >= 0 && y < H;     // wave-uniform
-                    const T* rowp = pz + (size_t)min(max(y, 0), H - 1) * W;
+                    const T* rowp = pz + (size_t)min(max(y, 0), H - 1) * rowst;
                     if constexpr (VEC) {
                         // W and xc are multiples of V: a lane's V columns are all in or all out
                         load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xv, dst[k]);
@@ -168,10 +172,10 @@ __global__ __launch_bounds__(kBlock) void ssam3d_kernel(
                     // output plane zin - RZ has now received its last contribution
                     const int zo = zin - RZ;
                     if (zo >= z0 && lane_stores) {
-                        T* po = a.out + (size_t)zo * plane + (size_t)y0 * W + xc;
+                        T* po = a.out + (size_t)zo * plane + (size_t)y0 * rowst + xc;
 #pragma unroll
                         for (int p = 0; p < P; ++p) {
-                            T* rowp = po + (size_t)p * W;
+                            T* rowp = po + (size_t)p * rowst;
                             if constexpr (!EDGE) {
                                 store_vec<T, V, (NT & kStreamStores) != 0>(rowp, acc[0][p]);
                             } else if (y0 + p < H) {
@@ -204,9 +208,14 @@ void fill_args3d(const Problem3D& pr, const Geometry& g, Args3D<T, SliceMask<RX,
     constexpr int NX = 2 * RX + 1, NY = 2 * RY + 1, NZ = 2 * RZ + 1;
     a->in = static_cast<const T*>(pr.in);
     a->out = static_cast<T*>(pr.out);
+    // march along z: strip axis y.  march along y (pr.march_y): strip axis z; the kernel then sees
+    // extents and coefficients with y and z exchanged, and the real strides.
+    const bool my = pr.march_y;
     a->W = pr.W;
-    a->H = pr.H;
-    a->D = pr.D;
+    a->H = my ? pr.D : pr.H;
+    a->D = my ? pr.H : pr.D;
+    a->stride_row = my ? (long)pr.W * pr.H : (long)pr.W;
+    a->stride_plane = my ? (long)pr.W : (long)pr.W * pr.H;
     a->boundary = pr.boundary;
     a->strips_x = g.strips_x;
     a->tiles_y = g.tiles_y;
@@ -216,9 +225,9 @@ void fill_args3d(const Problem3D& pr, const Geometry& g, Args3D<T, SliceMask<RX,
     a->blocks = g.blocks;
     a->xcd_remap = g.xcd_remap;
     a->aligned = pointers_aligned(pr.in, pr.out, V * sizeof(T)) ? 1 : 0;
-    const T* c = static_cast<const T*>(pr.c);   // host, dense [NZ][NY][NX]
+    const T* c = static_cast<const T*>(pr.c);   // host, dense [2rz+1][2ry+1][2rx+1] in real axes
     for (int i = 0; i < Mask0::kNW; ++i) a->w[i] = T(0);
-    for (int k = 0; k < NZ; ++k)
+    for (int k = 0; k < NZ; ++k)          // k: offset along the march axis, n: along the strip axis
         for (int n = 0; n < NY; ++n)
             for (int m = 0; m < NX; ++m) {
                 const int used = (k != RZ) + (n != RY) + (m != RX);
@@ -226,7 +235,7 @@ void fill_args3d(const Problem3D& pr, const Geometry& g, Args3D<T, SliceMask<RX,
                 int idx;
                 if (BUDGET == 1) idx = k != RZ ? k : (n != RY ? NZ + n : (m != RX ? NZ + NY + m : RZ));
                 else idx = (k * NX + m) * NY + n;
-                a->w[idx] = c[(k * NY + n) * NX + m];
+                a->w[idx] = my ? c[(n * NZ + k) * NX + m] : c[(k * NY + n) * NX + m];
             }
 }
 
@@ -239,11 +248,12 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g);
     g.P = P;
     g.rows_per_wave = P;
-    g.tiles_y = ceil_div(pr.H, P);
+    const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
+    g.tiles_y = ceil_div(LH, P);
     int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
-    if (planes > pr.D) planes = pr.D;
+    if (planes > LD) planes = LD;
     g.planes_per_wave = planes;
-    g.tiles_z = ceil_div(pr.D, planes);
+    g.tiles_z = ceil_div(LD, planes);
     plan_blocks(&g, tu.xcd_remap);
     if (geo) *geo = g;
     if (dry_run) return hipSuccess;

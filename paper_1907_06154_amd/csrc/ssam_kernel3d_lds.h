@@ -58,7 +58,10 @@ __global__ __launch_bounds__(NW* kWave) void ssam3d_lds_kernel(
     const T* __restrict__ in = a.in;
     typedef Args3D<T, SliceMask<RX, RY, RZ, BUDGET, 0>::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
-    const size_t plane = (size_t)W * H;
+    // strides of the two outer axes in elements: the rows of a lane's strip are `rowst` apart, the
+    // planes the wave marches over `plane` apart (W and W*H when marching z; swapped when the host
+    // asks for a march along y, where a.H and a.D are then the extents of z and y)
+    const size_t rowst = (size_t)a.stride_row, plane = (size_t)a.stride_plane;
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
     const unsigned left_mask = xc < 0 ? ~0u : 0u, right_mask = xc >= W ? ~0u : 0u;
     const unsigned left_pick = clamp ? left_mask : 0u, right_pick = clamp ? right_mask : 0u;
@@ -77,10 +80,10 @@ __global__ __launch_bounds__(NW* kWave) void ssam3d_lds_kernel(
         // this wave's share of plane z: staged rows wave, wave+NW, ... (row index within the block)
         auto fetch = [&](int z, T (&g)[RPW][V]) __attribute__((always_inline)) {
             if constexpr (!EDGE) {
-                const T* pz = in + (size_t)z * plane + (size_t)(yb0 - RY + wave) * W + xl;
+                const T* pz = in + (size_t)z * plane + (size_t)(yb0 - RY + wave) * rowst + xl;
 #pragma unroll
                 for (int i = 0; i < RPW; ++i)
-                    load_vec<T, V, (NT & kStreamLoads) != 0>(pz + (size_t)(i * NW) * W, g[i]);
+                    load_vec<T, V, (NT & kStreamLoads) != 0>(pz + (size_t)(i * NW) * rowst, g[i]);
             } else {
                 const bool plane_in = z >= 0 && z < D;
                 const T* pz = in + (size_t)min(max(z, 0), D - 1) * plane;
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(NW* kWave) void ssam3d_lds_kernel(
                 for (int i = 0; i < RPW; ++i) {
                     const int y = yb0 - RY + wave + i * NW;
                     const bool row_in = plane_in && y >= 0 && y < H;     // wave-uniform
-                    const T* rowp = pz + (size_t)min(max(y, 0), H - 1) * W;
+                    const T* rowp = pz + (size_t)min(max(y, 0), H - 1) * rowst;
                     if constexpr (VEC) {
                         load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + xv, g[i]);
                         const T first = g[i][0], last = g[i][V - 1];
@@ -159,10 +162,10 @@ __global__ __launch_bounds__(NW* kWave) void ssam3d_lds_kernel(
 
                     const int zo = zin - RZ;
                     if (zo >= z0 && lane_stores) {
-                        T* po = a.out + (size_t)zo * plane + (size_t)y0 * W + xc;
+                        T* po = a.out + (size_t)zo * plane + (size_t)y0 * rowst + xc;
 #pragma unroll
                         for (int p = 0; p < P; ++p) {
-                            T* rowp = po + (size_t)p * W;
+                            T* rowp = po + (size_t)p * rowst;
                             if constexpr (!EDGE) {
                                 store_vec<T, V, (NT & kStreamStores) != 0>(rowp, acc[0][p]);
                             } else if (y0 + p < H) {
@@ -197,11 +200,12 @@ hipError_t launch3d_lds(const Problem3D& pr, const Tuning& tu, Geometry* geo, bo
     plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g);
     g.P = P;
     g.rows_per_wave = P;
-    g.tiles_y = ceil_div(pr.H, NW * P);          // y blocks of NW waves
+    const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
+    g.tiles_y = ceil_div(LH, NW * P);            // blocks of NW waves along the strip axis
     int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
-    if (planes > pr.D) planes = pr.D;
+    if (planes > LD) planes = LD;
     g.planes_per_wave = planes;
-    g.tiles_z = ceil_div(pr.D, planes);
+    g.tiles_z = ceil_div(LD, planes);
     g.tiles = (long)g.strips_x * g.tiles_y * g.tiles_z;   // block tiles
     g.xcd_remap = tu.xcd_remap < 0 ? 1 : (tu.xcd_remap ? 1 : 0);
     g.blocks = g.xcd_remap ? ceil_div((int)g.tiles, kXcds) * kXcds : (int)g.tiles;

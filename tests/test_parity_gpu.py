@@ -21,7 +21,7 @@ def ssam():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     s.lib()   # raises if the HIP library is missing: there is no fallback
     yield s
-    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant"):
+    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant", "march_axis"):
         s.ssam_set_tuning(name, -1)
 
 
@@ -127,6 +127,8 @@ def test_stencil3d(ssam, dtype, kind, r, boundary):
     {"rows_per_wave": 16, "valid_lanes": 40, "planes_per_wave": 3, "xcd_remap": 0}, {"force_generic": 1},
     {"variant": 1}, {"variant": 2}, {"variant": 3}, {"variant": 7}, {"variant": 8},
     {"variant": 7, "planes_per_wave": 5, "valid_lanes": 24}, {"variant": 8, "planes_per_wave": 2, "xcd_remap": 0},
+    {"march_axis": 1}, {"march_axis": 1, "variant": 1}, {"march_axis": 1, "variant": 7, "planes_per_wave": 6},
+    {"march_axis": 1, "variant": 8},
 ])
 def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
     try:
