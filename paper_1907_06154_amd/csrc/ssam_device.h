@@ -27,8 +27,15 @@ enum : int { kZero = 0, kClamp = 1 };
 // shift_down: lane L receives the value lane L+1 held (lane 63 receives 0).
 // DPP control 0x138 = wave_shr:1, 0x130 = wave_shl:1 (GFX9 encoding).  bound_ctrl makes the
 // lane without a source read 0, so no "old" value has to be materialised first.
+#if defined(SSAM_SHIFT_BPERMUTE)
+// Comparison build only: the same shift through the LDS crossbar (what a recompiled
+// __shfl_up / __shfl_down does).  The values read by lanes 0 / 63 are never used.
+__device__ __forceinline__ int dpp_up(int v) { return __builtin_amdgcn_ds_bpermute(((int)(threadIdx.x & 63) - 1) << 2, v); }
+__device__ __forceinline__ int dpp_down(int v) { return __builtin_amdgcn_ds_bpermute(((int)(threadIdx.x & 63) + 1) << 2, v); }
+#else
 __device__ __forceinline__ int dpp_up(int v) { return __builtin_amdgcn_mov_dpp(v, 0x138, 0xf, 0xf, true); }
 __device__ __forceinline__ int dpp_down(int v) { return __builtin_amdgcn_mov_dpp(v, 0x130, 0xf, 0xf, true); }
+#endif
 
 __device__ __forceinline__ float shift_up(float v) { return __builtin_bit_cast(float, dpp_up(__builtin_bit_cast(int, v))); }
 __device__ __forceinline__ float shift_down(float v) { return __builtin_bit_cast(float, dpp_down(__builtin_bit_cast(int, v))); }

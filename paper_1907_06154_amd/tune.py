@@ -1,0 +1,72 @@
+"""Times benchmark cases under tuning overrides (launch geometry, compiled-instance variants).
+
+    python -m paper_1907_06154_amd.tune <config> <case-substring> "<knob>=v1,v2;<knob2>=..." [reps]
+
+e.g.  python -m paper_1907_06154_amd.tune config2 conv3x3 "rows_per_wave=32,64;valid_lanes=56,62" 20
+
+Every combination of the listed knob values (see ssam_set_tuning in include/ssam.h) is timed
+with HIP events on the launch stream; iterative cases run min(steps, 4) sweeps per repetition.
+A library built with other compile-time options can be compared by pointing SSAM_LIB_PATH at it
+(python -m paper_1907_06154_amd.build other.so -DNAME).
+"""
+from __future__ import annotations
+
+import itertools
+import sys
+
+import numpy as np
+
+
+def main(argv) -> int:
+    import torch
+
+    import paper_1907_06154_amd as ssam
+    from paper_1907_06154_amd import workloads as wl
+
+    if len(argv) < 3:
+        print(__doc__)
+        return 2
+    cfg, sub, spec = argv[0], argv[1], argv[2]
+    reps = int(argv[3]) if len(argv) > 3 else 10
+    cases = [c for c in wl.all_configs()[cfg] if sub in c.name]
+    keys, vals = [], []
+    for item in spec.split(";"):
+        if item:
+            k, v = item.split("=")
+            keys.append(k)
+            vals.append([int(x) for x in v.split(",")])
+    for c in cases:
+        fld = torch.from_numpy(c.field()).cuda()
+        a, b = fld.clone(), torch.empty_like(fld)
+        coef = c.coef if c.kind != "stencil2d" else c.coef[0]
+        sweeps = 1 if c.kind == "conv2d" else min(c.steps, 4)
+
+        def run():
+            if c.kind == "conv2d":
+                ssam.ssam_conv2d(a, coef, c.boundary, d_out=b)
+            else:
+                ssam.ssam_stencil_iterate(a, b, coef, sweeps, c.boundary)
+
+        for combo in itertools.product(*vals):
+            for k, v in zip(keys, combo):
+                ssam.ssam_set_tuning(k, v)
+            for _ in range(2):
+                run()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps / sweeps
+            gpt = c.points / ms / 1e6
+            gbs = gpt * 2 * np.dtype(c.dtype).itemsize
+            knobs = " ".join(f"{k}={v}" for k, v in zip(keys, combo))
+            print(f"{c.name:26s} {knobs}  {ms * 1e3:8.1f} us {gpt:7.1f} GStencil/s {gbs:7.0f} GB/s", flush=True)
+        for k in keys:
+            ssam.ssam_set_tuning(k, -1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))
