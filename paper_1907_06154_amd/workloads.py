@@ -211,6 +211,37 @@ def config5(n: int = 512, steps: int = 20) -> List[Case]:
             for dt in (np.float32, np.float64)]
 
 
+def filter_sweep(n: int = 8192) -> List[Case]:
+    """The paper's full filter sweep (Sec. 6.2): square filters 2x2 .. 20x20 on an n x n fp32 image."""
+    out = []
+    for m in range(2, 21):
+        f = seeded_filter(m, m, 200 + m, np.float32)
+        out.append(Case(f"fs_conv{m}x{m}_f32", "conv2d", np.float32, (n, n), (0.0, 1.0), 3, f, "clamp", 1,
+                        "Fig. 4 filter sweep on 8192^2"))
+    return out
+
+
+def table3(n2: int = 8192, n3: int = 512, steps: int = 10, dtypes=(np.float32, np.float64)) -> List[Case]:
+    """The stencil shapes of Table 3 that a radius describes (2d64pt is not one of them): 2D stars of
+    order 1..6, 2D boxes of order 2, 4, 5, 3D stars of order 1, 2, 3D boxes of order 1, 2 and the
+    19-point shape, in both precisions, `steps` sweeps with seeded coefficients of sum 1."""
+    specs2 = [("2d5pt", mask_star(1, 1)), ("2d9pt", mask_star(2, 2)), ("2d13pt", mask_star(3, 3)),
+              ("2d17pt", mask_star(4, 4)), ("2d21pt", mask_star(5, 5)), ("2ds25pt", mask_star(6, 6)),
+              ("2d25pt", mask_box(2, 2)), ("2d81pt", mask_box(4, 4)), ("2d121pt", mask_box(5, 5))]
+    specs3 = [("3d7pt", mask_star(1, 1, 1)), ("3d13pt", mask_star(2, 2, 2)), ("3d27pt", mask_box(1, 1, 1)),
+              ("3d125pt", mask_box(2, 2, 2)), ("poisson", mask_faces_edges())]
+    out = []
+    for dt in dtypes:
+        tag = "f32" if dt == np.float32 else "f64"
+        for i, (nm, m) in enumerate(specs2):
+            out.append(Case(f"t3_{nm}_{tag}", "stencil2d", dt, (n2, n2), (-1.0, 1.0), 5,
+                            seeded_coefficients(m, 300 + i, dt), "zero", steps, f"Table 3 {nm}"))
+        for i, (nm, m) in enumerate(specs3):
+            out.append(Case(f"t3_{nm}_{tag}", "stencil3d", dt, (n3, n3, n3), (-1.0, 1.0), 6,
+                            seeded_coefficients(m, 320 + i, dt), "zero", steps, f"Table 3 {nm}"))
+    return out
+
+
 def all_configs() -> Dict[str, List[Case]]:
     return {"config1": config1(), "config2": config2(), "config3": config3(),
-            "config4": config4(), "config5": config5()}
+            "config4": config4(), "config5": config5(), "filter_sweep": filter_sweep(), "table3": table3()}

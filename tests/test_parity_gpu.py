@@ -37,7 +37,7 @@ def host(t):
 SHAPES_2D = [(70, 300), (37, 259), (5, 7), (1, 1), (64, 1024), (129, 520), (3, 2050)]
 
 
-@pytest.mark.parametrize("MN", wl.CONV_SHAPES + [(2, 2), (4, 6), (7, 7), (1, 5), (5, 1)])
+@pytest.mark.parametrize("MN", sorted(set(wl.CONV_SHAPES + [(m, m) for m in range(2, 21)] + [(4, 6), (1, 5), (5, 1), (21, 21)])))
 @pytest.mark.parametrize("boundary", ["clamp", "zero"])
 def test_conv2d_f32(ssam, MN, boundary):
     M, N = MN
@@ -63,8 +63,8 @@ def test_conv2d_f64_and_anchors(ssam, MN):
             assert_parity(got, want, filt, 1.0, f"conv f64 {M}x{N} {anchor} {boundary}")
 
 
-STENCILS_2D = [("star", 1), ("star", 2), ("star", 3), ("star", 4), ("box", 1), ("box", 2), ("box", 3), ("box", 4),
-               ("star_wide", 0), ("sparse", 2)]
+STENCILS_2D = [("star", 1), ("star", 2), ("star", 3), ("star", 4), ("star", 5), ("star", 6), ("star", 7),
+               ("box", 1), ("box", 2), ("box", 3), ("box", 4), ("box", 5), ("star_wide", 0), ("sparse", 2)]
 
 
 def stencil2d_coef(kind, r, dtype, seed):
@@ -94,7 +94,8 @@ def test_stencil2d(ssam, dtype, kind, r, boundary):
 
 
 SHAPES_3D = [(9, 10, 130), (70, 6, 30), (3, 3, 3), (1, 5, 5), (20, 13, 259), (12, 11, 140), (6, 5, 516)]
-STENCILS_3D = [("star", 1), ("box", 1), ("faces_edges", 1), ("star", 4), ("star", 2), ("box_aniso", 0)]
+STENCILS_3D = [("star", 1), ("box", 1), ("faces_edges", 1), ("star", 4), ("star", 2), ("box", 2), ("star", 3),
+               ("box_aniso", 0)]
 
 
 def stencil3d_coef(kind, r, dtype, seed):
