@@ -110,7 +110,13 @@ def cpu_baseline(cases, target_seconds: float):
         secs += dt
         pts += n
         desc.append("x".join(str(v) for v in (lead,) + tuple(case.shape[1:])))
-    return {"value": pts / secs / 1e9, "unit": "GStencil/s", "cores": oracle.num_threads(), "kind": "oracle",
+    # one thread on a reduced extent, for the per-point cost of the oracle itself
+    threads = oracle.num_threads()
+    oracle.set_num_threads(1)
+    dt1, n1 = run(c0, max(1, lead0 // max(1, threads)))
+    oracle.set_num_threads(threads)
+    return {"value": pts / secs / 1e9, "unit": "GStencil/s", "cores": threads, "kind": "oracle",
+            "single_thread_ns_per_point": dt1 / n1 * 1e9, "single_thread_case": c0.name,
             "sample": f"one sweep of each of the {len(cases)} cases on the leading block of its grid "
                       f"({', '.join(desc)}; {pts} points, {secs:.1f} s of oracle time)"}
 
