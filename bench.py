@@ -33,8 +33,9 @@ ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}   # published vector peaks (fp32 f
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors being what the same counters read for ssam_probe_copy of known size); the runs and
-# their commands are summarised under profiles/.  Keyed by case name; offline figures, not
-# re-measured by this script.
+# their commands are summarised under profiles/.  Keyed by case name and, for the multi-sweep
+# kernels of the iterative 2D cases, by case and kernel instance; offline figures, not re-measured
+# by this script.
 MEASURED_TRAFFIC_BYTES = {
     "c2_conv3x3_f32": 554059143,
     "c2_conv5x5_f32": 565128212,
@@ -46,6 +47,9 @@ MEASURED_TRAFFIC_BYTES = {
     "c3_2d_box_r1_f64": 1102485294,
     "c3_2d_box_r2_f64": 1083534618,
     "c3_2d_star_r4_f64": 1129549854,
+    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1151098980,
+    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1210095674,
+    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1254116967,
     "c4_3d_star_r1_f64": 2436739858,
     "c4_3d_box_r1_f64": 2379723841,
     "c4_3d_faces_edges_f64": 2382340545,
@@ -72,7 +76,8 @@ def run_case(ssam, case, bufs):
     elif case.steps == 1:
         ssam.ssam_stencil3d(a, case_coef(case), case.boundary, d_out=b)
     else:
-        ssam.ssam_stencil_iterate(a, b, case_coef(case), case.steps, case.boundary)
+        return ssam.ssam_stencil_iterate(a, b, case_coef(case), case.steps, case.boundary)
+    return b
 
 
 def cpu_baseline(cases, target_seconds: float):
@@ -128,6 +133,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "filter_sweep", "table3"])
     ap.add_argument("--cases", default=None, help="comma-separated substrings selecting cases of the workload")
+    ap.add_argument("--fuse-sweeps", type=int, default=-1,
+                    help="cap on the sweeps ssam_stencil_iterate fuses into one launch (0: none; default: the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
     args = ap.parse_args()
@@ -147,6 +154,7 @@ def main() -> int:
         return 2
     ssam.lib()
     torch.cuda.set_device(0)
+    ssam.ssam_set_tuning("fuse_sweeps", args.fuse_sweeps)
 
     cases = wl.all_configs()[args.workload]
     if args.cases:
@@ -182,10 +190,10 @@ def main() -> int:
             return fields[bufs[c.name]], work[bufs[c.name]][1]
         return current[c.name]
 
-    def finish(c):
-        if c.steps > 1 and c.steps % 2 == 1:
+    def finish(c, res):
+        if c.steps > 1:   # carry on from whichever buffer holds the field now
             a, b = current[c.name]
-            current[c.name] = (b, a)
+            current[c.name] = (res, b if res is a else a)
 
     stream = torch.cuda.current_stream()
 
@@ -204,8 +212,7 @@ def main() -> int:
 
     for _ in range(warmup):
         for c in cases:
-            run_case(ssam, c, prepare(c))
-            finish(c)
+            finish(c, run_case(ssam, c, prepare(c)))
     torch.cuda.synchronize()
 
     ev = {c.name: [] for c in cases}
@@ -216,9 +223,9 @@ def main() -> int:
             pair = prepare(c)
             s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             s.record(stream)
-            run_case(ssam, c, pair)
+            res = run_case(ssam, c, pair)
             e.record(stream)
-            finish(c)
+            finish(c, res)
             ev[c.name].append((s, e))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -227,20 +234,30 @@ def main() -> int:
     total_pts = 0
     for c in cases:
         ms = float(np.mean([s.elapsed_time(e) for s, e in ev[c.name]]))
-        per_launch_ms = ms / c.steps
+        # a launch is one sweep, or several where ssam_stencil_iterate fuses 2D sweeps: such a
+        # launch still reads and writes the grid once, and does the arithmetic of all its sweeps
+        kind = "iterate2d" if (c.kind == "stencil2d" and c.steps > 1) else c.kind
+        kname = ssam.ssam_describe(kind, c.shape, case_coef(c), c.boundary).split()[0]
+        launches, t = 0, 0
+        while t < c.steps:   # replay the planner: a "..._fusedS" launch performs S sweeps
+            nm = ssam.ssam_describe(kind, c.shape, case_coef(c), c.boundary, remaining=c.steps - t).split()[0] \
+                if kind == "iterate2d" else kname
+            t += int(nm.rsplit("_fused", 1)[1]) if "_fused" in nm else 1
+            launches += 1
+        per_launch_ms = ms / launches
         esz = np.dtype(c.dtype).itemsize
         alg_bytes = c.points * 2 * esz
-        flops = c.points * (2 * c.taps - 1)
+        flops = c.points * (2 * c.taps - 1) * c.steps / launches
         tag = dtype_tag(c.dtype)
         t_hbm = alg_bytes / (HBM_PEAK_GBPS * 1e9)
         t_alu = flops / (ALU_PEAK_TFLOPS[tag] * 1e12)
         gbps = alg_bytes / (per_launch_ms * 1e-3) / 1e9
         tflops = flops / (per_launch_ms * 1e-3) / 1e12
-        k = {"case": c.name, "kernel": ssam.ssam_describe(c.kind, c.shape, case_coef(c), c.boundary).split()[0],
-             "launch_ms": per_launch_ms, "launches_per_step": c.steps, "gstencil_per_s": c.points / per_launch_ms / 1e6,
+        k = {"case": c.name, "kernel": kname, "launch_ms": per_launch_ms, "launches_per_step": launches,
+             "sweeps_per_launch": c.steps / launches, "gstencil_per_s": c.points * c.steps / ms / 1e6,
              "hbm_GBps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS, "alu_TFLOPs": tflops,
              "alu_frac": tflops / ALU_PEAK_TFLOPS[tag], "bound": "hbm" if t_hbm >= t_alu else "alu",
-             "traffic": MEASURED_TRAFFIC_BYTES.get(c.name)}
+             "traffic": MEASURED_TRAFFIC_BYTES.get(c.name + ":" + kname if "_fused" in kname else c.name)}
         kernels.append(k)
         total_pts += c.points * c.steps
 
@@ -262,7 +279,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: " + ", ".join(c.name for c in cases),
                    "grid": "x".join(str(s) for s in cases[0].shape), "boundary": cases[0].boundary,
-                   "sweeps_per_case": cases[0].steps},
+                   "sweeps_per_case": cases[0].steps, "fuse_sweeps": args.fuse_sweeps},
         "roofline": roof,
         "copy_ceiling_GBps": copy_gbps,
         "kernels": kernels,

@@ -77,13 +77,16 @@ int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
                    const void *h_coef, int rx, int ry, int rz,
                    int boundary, int dtype, void *hip_stream);
 
-/* `steps` Jacobi sweeps (paper Sec. 2.2: s_{i+1} computed from s_i) with two buffers:
- * sweep 0 reads d_a and writes d_b, sweep 1 reads d_b and writes d_a, and so on; every grid
- * point is updated each sweep, the boundary rule supplying reads outside the grid.  D == 1
- * with rz == 0 is the 2D case.  *d_result (host location, may be NULL) receives the buffer
- * that holds the field after `steps` sweeps: d_a for even counts (steps == 0 does nothing),
- * d_b for odd counts.  Both buffers are overwritten when steps >= 2.  No host
- * synchronisation happens between sweeps. */
+/* `steps` Jacobi sweeps (paper Sec. 2.2: s_{i+1} computed from s_i) with two buffers, each
+ * launch reading one and writing the other; every grid point is updated each sweep, the
+ * boundary rule supplying reads outside the grid.  D == 1 with rz == 0 is the 2D case.
+ * A launch performs one sweep, or -- 2D, zero padding, a compiled multi-sweep instance for the
+ * shape -- several sweeps with the intermediate fields held in registers (temporal blocking,
+ * which Sec. 6.4 says the model permits); the result is the same field to rounding either way.
+ * *d_result (host location, may be NULL) receives the buffer that holds the field after
+ * `steps` sweeps: d_a when the number of LAUNCHES is even (steps == 0 does nothing), d_b when
+ * it is odd -- read it rather than infer it from `steps`.  Both buffers are overwritten when
+ * more than one launch runs.  No host synchronisation happens between sweeps. */
 int ssam_stencil_iterate(void *d_a, void *d_b, int W, int H, int D,
                          const void *h_coef, int rx, int ry, int rz,
                          int boundary, int dtype, int steps,
@@ -96,7 +99,7 @@ const char *ssam_status_string(int status);
  * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
  * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant" (an alternative
  * compiled instance of the same shape, where one exists), "march_axis" (3D: 0 = march along z,
- * 1 = march along y).
+ * 1 = march along y), "fuse_sweeps" (ssam_stencil_iterate: 0 or 1 = always one sweep per launch, n >= 2 = at most n).
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 
@@ -105,7 +108,9 @@ int ssam_set_tuning(const char *name, int value);
  * dispatcher would use -- e.g. "float_M3N3_b2_v4p8 V=4 P=8 halo_lanes=1+1 valid_lanes=61
  * strips_x=34 ..." -- into buf (at most buflen bytes).  kind 0 = ssam_conv2d with (a, b) =
  * (M, N) and the default anchor; kind 1 = ssam_stencil2d with (a, b) = (rx, ry); kind 2 =
- * ssam_stencil3d with (a, b, c) = (rx, ry, rz).  The tile plan follows the paper's overlapped
+ * ssam_stencil3d with (a, b, c) = (rx, ry, rz); kind 3 = the launch ssam_stencil_iterate uses
+ * on a 2D grid with (a, b) = (rx, ry) while c sweeps remain (c <= 0: many); an instance named
+ * "..._fusedS" performs S sweeps.  The tile plan follows the paper's overlapped
  * blocking (Sec. 4.5, Sec. 4.7) re-derived for 64 lanes of V columns each. */
 int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
                   int boundary, int dtype, char *buf, int buflen);

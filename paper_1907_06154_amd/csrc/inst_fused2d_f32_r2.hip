@@ -1,0 +1,11 @@
+// Multi-sweep (temporally blocked) 2D stencil instances: inst_fused2d_f32_r2.hip
+#include "ssam_kernel2d_fused.h"
+
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 1, 2, 2, 0);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 2, 1, 2, 2, 1);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 1, 3, 2, 0);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 1, 4, 2, 0);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 2, 2, 2, 0);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 2, 2, 2, 2, 1);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 2, 3, 2, 0);
+SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 2, 2, 4, 2, 0);

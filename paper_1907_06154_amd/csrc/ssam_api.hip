@@ -24,8 +24,9 @@ std::vector<Instance3D>& registry3d()
 
 namespace {
 
+constexpr int kMaxFusedSweeps = 8;
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
-    g_force_generic{-1}, g_variant{-1}, g_march_axis{-1};
+    g_force_generic{-1}, g_variant{-1}, g_march_axis{-1}, g_fuse_sweeps{-1};
 
 Tuning current_tuning()
 {
@@ -37,6 +38,7 @@ Tuning current_tuning()
     t.force_generic = g_force_generic.load();
     t.variant = g_variant.load();
     t.march_axis = g_march_axis.load();
+    t.fuse_sweeps = g_fuse_sweeps.load();
     return t;
 }
 
@@ -204,7 +206,7 @@ size_t elem(int dtype) { return dtype == SSAM_F32 ? 4 : 8; }
 
 // ---- dispatch ---------------------------------------------------------------------------
 template <typename T>
-const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant)
+const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant, int sweeps = 1)
 {
     const T* w = static_cast<const T*>(p.w);
     int budget = 2;
@@ -217,7 +219,7 @@ const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_va
         if (i.dtype != p.dtype || i.M != p.M || i.N != p.N || i.AX != p.ax) continue;
         if (i.budget < budget) continue;
         if (i.budget == 1 && p.ay != p.N / 2) continue;   // star instances assume the centre row
-        if (i.variant != want_variant) continue;
+        if (i.variant != want_variant || i.sweeps != sweeps) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
@@ -271,6 +273,31 @@ const Instance3D* pick3d(const Problem3D& p, int want_variant)
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
+}
+
+// Several sweeps in one launch, where the shape has a fused instance (2D, zero padding): the
+// deepest compiled one that does not exceed `max_sweeps` (the sweeps still to do) nor the
+// "fuse_sweeps" cap.  Returns the number of sweeps the launch performs, 0 when the caller should
+// run a single sweep instead.
+int run2d_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::string* name, int* rc)
+{
+    const Tuning tu = current_tuning();
+    if (tu.fuse_sweeps == 0 || tu.fuse_sweeps == 1 || tu.force_generic > 0 || p.D != 1 || p.rz != 0 ||
+        p.boundary != SSAM_BOUNDARY_ZERO)
+        return 0;
+    if (tu.fuse_sweeps > 1 && tu.fuse_sweeps < max_sweeps) max_sweeps = tu.fuse_sweeps;
+    if (max_sweeps > kMaxFusedSweeps) max_sweeps = kMaxFusedSweeps;
+    Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
+    const int v = tu.variant > 0 ? tu.variant : 0;
+    for (int sweeps = max_sweeps; sweeps >= 2; --sweeps) {
+        const Instance2D* inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, v, sweeps) : pick2d<double>(q, true, v, sweeps);
+        if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, sweeps) : pick2d<double>(q, true, 0, sweeps);
+        if (!inst) continue;
+        if (name) *name = inst->name;
+        *rc = inst->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        return sweeps;
+    }
+    return 0;
 }
 
 int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
@@ -387,9 +414,16 @@ int ssam_stencil_iterate(void* d_a, void* d_b, int W, int H, int D, const void* 
     if (steps < 0) return SSAM_ERR_SHAPE;
     void* src = d_a;
     void* dst = d_b;
-    for (int t = 0; t < steps; ++t) {
+    for (int t = 0; t < steps;) {
         Problem3D p{src, dst, W, H, D, h_coef, rx, ry, rz, boundary, dtype, (hipStream_t)hip_stream};
-        if (int e = run3d(p, nullptr, false, nullptr)) return e;
+        int rc = SSAM_OK;
+        if (const int fused = run2d_fused(p, steps - t, nullptr, false, nullptr, &rc)) {
+            if (rc) return rc;
+            t += fused;
+        } else {
+            if (int e = run3d(p, nullptr, false, nullptr)) return e;
+            t += 1;
+        }
         void* tmp = src;
         src = dst;
         dst = tmp;
@@ -435,6 +469,7 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "force_generic")) g_force_generic = value;
     else if (!strcmp(name, "variant")) g_variant = value;
     else if (!strcmp(name, "march_axis")) g_march_axis = value;
+    else if (!strcmp(name, "fuse_sweeps")) g_fuse_sweeps = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }
@@ -464,6 +499,16 @@ int ssam_describe(int kind, int W, int H, int D, const void* h_coef, int a, int 
         if (a < 0 || b < 0 || c < 0 || a > SSAM_MAX_RADIUS || b > SSAM_MAX_RADIUS || c > SSAM_MAX_RADIUS)
             return SSAM_ERR_SHAPE;
         Problem3D p{nullptr, out, W, H, D, h_coef, a, b, c, boundary, dtype, nullptr};
+        return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
+    }
+    if (kind == 3) {   // the launch ssam_stencil_iterate uses while c (or more) 2D sweeps remain
+        if (!h_coef) return SSAM_ERR_NULL;
+        if (int e = check_enums(boundary, dtype)) return e;
+        if (int e = check_dims(W, H, 1)) return e;
+        if (a < 0 || b < 0 || a > SSAM_MAX_RADIUS || b > SSAM_MAX_RADIUS) return SSAM_ERR_SHAPE;
+        Problem3D p{nullptr, out, W, H, 1, h_coef, a, b, 0, boundary, dtype, nullptr};
+        int rc = SSAM_OK;
+        if (run2d_fused(p, c > 0 ? c : kMaxFusedSweeps, &g, true, &name, &rc)) return describe(rc, name, g, buf, buflen);
         return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
     }
     return SSAM_ERR_ENUM;

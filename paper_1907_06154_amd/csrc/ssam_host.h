@@ -22,6 +22,7 @@ struct Tuning {
     int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
     int variant = -1;          // pick an alternative compiled instance of the same shape
     int march_axis = -1;       // 3D: 0 march along z (strip along y), 1 march along y (strip along z)
+    int fuse_sweeps = -1;      // iteration: 0 = one sweep per launch, otherwise two where a fused instance exists
 };
 
 struct Problem2D {
@@ -68,6 +69,7 @@ struct Instance2D {
     int dtype, M, N, AX, budget;  // budget 2 = dense box, 1 = star
     int variant;                  // 0 = default instance for the shape
     Launch2DFn launch;
+    int sweeps = 1;               // Jacobi sweeps one launch performs (2: the fused kernel, zero padding only)
 };
 
 struct Instance3D {

@@ -5,7 +5,7 @@
 e.g.  python -m paper_1907_06154_amd.tune config2 conv3x3 "rows_per_wave=32,64;valid_lanes=56,62" 20
 
 Every combination of the listed knob values (see ssam_set_tuning in include/ssam.h) is timed
-with HIP events on the launch stream; iterative cases run min(steps, 4) sweeps per repetition.
+with HIP events on the launch stream; iterative cases run min(steps, 24) sweeps per repetition.
 A library built with other compile-time options can be compared by pointing SSAM_LIB_PATH at it
 (python -m paper_1907_06154_amd.build other.so -DNAME).
 """
@@ -39,7 +39,7 @@ def main(argv) -> int:
         fld = torch.from_numpy(c.field()).cuda()
         a, b = fld.clone(), torch.empty_like(fld)
         coef = c.coef if c.kind != "stencil2d" else c.coef[0]
-        sweeps = 1 if c.kind == "conv2d" else min(c.steps, 4)
+        sweeps = 1 if c.kind == "conv2d" else min(c.steps, 24)
 
         def run():
             if c.kind == "conv2d":

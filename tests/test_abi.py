@@ -129,3 +129,35 @@ def test_shape_classification(L):
     star = np.zeros((17, 17, 17)); star[8, 8, :] = 1; star[8, :, 8] = 1; star[:, 8, 8] = 1
     name, _ = parse(ssam.ssam_describe("stencil3d", (32, 32, 32), star, "zero"))
     assert name == "generic_direct"
+
+
+def test_fused_sweep_plan(L):
+    """2D sweeps with zero padding run several to a launch; the overlap grows with the depth S on
+    every side (S times the single-sweep halo); clamp and shapes without a fused instance keep
+    single sweeps; the planner never runs more sweeps than remain."""
+    import re
+    for c in wl.config3():
+        coef = c.coef[0]
+        r = coef.shape[0] // 2
+        one, g1 = parse(ssam.ssam_describe("stencil2d", c.shape, coef, "zero"))
+        assert "_fused" not in one
+        for remaining in (0, 2, 3, 4):
+            many, g = parse(ssam.ssam_describe("iterate2d", c.shape, coef, "zero", remaining=remaining))
+            S = int(re.search(r"_fused(\d+)$", many).group(1))
+            assert 2 <= S and (remaining == 0 or S <= remaining)
+            assert g["halo_lanes"] == S * g1["halo_lanes"] == 2 * S * -(-r // g["V"])
+            assert g["valid_lanes"] <= 64 - g["halo_lanes"]
+            assert g["strips_x"] * g["valid_lanes"] * g["V"] >= c.shape[1]
+            assert g["rows_per_wave"] % g["P"] == 0
+        assert parse(ssam.ssam_describe("iterate2d", c.shape, coef, "zero", remaining=1))[0] == one
+        same, _ = parse(ssam.ssam_describe("iterate2d", c.shape, coef, "clamp"))
+        assert same == parse(ssam.ssam_describe("stencil2d", c.shape, coef, "clamp"))[0]
+    coef = wl.config3()[0].coef[0]
+    for cap, ok in ((0, lambda n: "_fused" not in n), (1, lambda n: "_fused" not in n), (2, lambda n: n.endswith("_fused2"))):
+        ssam.ssam_set_tuning("fuse_sweeps", cap)
+        try:
+            assert ok(parse(ssam.ssam_describe("iterate2d", (512, 512), coef, "zero"))[0])
+        finally:
+            ssam.ssam_set_tuning("fuse_sweeps", -1)
+    wide = np.ones((15, 15))   # radius 7: no fused instance
+    assert parse(ssam.ssam_describe("iterate2d", (512, 512), wide, "zero"))[0] == "generic_direct"

@@ -167,12 +167,77 @@ def test_iterate_matches_oracle_and_ping_pongs(ssam, dtype):
             print(f"iterate {np.dtype(dtype).name} {shape} steps {steps}", flush=True)
             a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
             res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
-            assert res.data_ptr() == (a if steps % 2 == 0 else b).data_ptr()
+            assert res.data_ptr() in (a.data_ptr(), b.data_ptr()) and (steps or res.data_ptr() == a.data_ptr())
             want = oracle.iterate(fld, coef, steps, "zero")
             if steps == 0:
                 assert np.array_equal(host(res), fld)
             else:
                 assert_parity(host(res), want, coef, 1.0, f"iterate {shape} {steps}")
+
+
+FUSED_SHAPES = [(1, 1), (3, 5), (9, 130), (33, 224), (70, 300), (131, 449), (150, 1000), (260, 96)]
+
+
+def planned_launches(ssam, shape, coef, steps, boundary):
+    """Launches ssam_stencil_iterate issues for `steps` 2D sweeps, from the planning query."""
+    import re
+    t = n = 0
+    while t < steps:
+        name = ssam.ssam_describe("iterate2d", shape, coef, boundary, remaining=steps - t).split()[0]
+        m = re.search(r"_fused(\d+)$", name)
+        t += int(m.group(1)) if m else 1
+        n += 1
+    assert t == steps
+    return n
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind,r", [("box", 1), ("star", 1), ("box", 2), ("star", 2), ("star", 3), ("star", 4)])
+def test_fused_sweeps_match_oracle(ssam, dtype, kind, r):
+    """Several 2D sweeps run as one launch (zero padding): every step count and fusion depth, grids
+    smaller than a tile, ragged tails, rows that are not vector-aligned; and fusion switched off."""
+    mask = wl.mask_box(r, r) if kind == "box" else wl.mask_star(r, r)
+    coef = wl.seeded_coefficients(mask, 820 + r, dtype)[0]
+    assert "_fused" in ssam.ssam_describe("iterate2d", (512, 512), coef, "zero")
+    assert "_fused" not in ssam.ssam_describe("iterate2d", (512, 512), coef, "clamp")
+    for shape in FUSED_SHAPES:
+        fld = wl.uniform_field(shape, -1.0, 1.0, 830 + shape[0], dtype)
+        for steps in (2, 3, 4, 5, 6, 7, 9):
+            want = oracle.iterate(fld, coef, steps, "zero")
+            for fuse in (-1, 0, 2, 3):
+                print(f"fused {np.dtype(dtype).name} {kind} r{r} {shape} steps {steps} fuse {fuse}", flush=True)
+                ssam.ssam_set_tuning("fuse_sweeps", fuse)
+                try:
+                    launches = planned_launches(ssam, shape, coef, steps, "zero")
+                    a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+                    res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
+                finally:
+                    ssam.ssam_set_tuning("fuse_sweeps", -1)
+                assert launches == steps if fuse == 0 else launches < steps
+                assert res.data_ptr() == (a if launches % 2 == 0 else b).data_ptr()
+                assert_parity(host(res), want, coef, 1.0, f"fused {kind} r{r} {shape} steps {steps} fuse {fuse}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_fused_sweeps_tile_overrides_and_clamp(ssam, dtype):
+    coef = wl.seeded_coefficients(wl.mask_box(2, 2), 841, dtype)[0]
+    fld = wl.uniform_field((300, 1200), -1.0, 1.0, 842, dtype)
+    want = oracle.iterate(fld, coef, 4, "zero")
+    for tuning in ({"rows_per_wave": 8}, {"rows_per_wave": 40, "valid_lanes": 17}, {"xcd_remap": 0}, {"variant": 1},
+                   {"fuse_sweeps": 2, "variant": 1}, {"fuse_sweeps": 3, "rows_per_wave": 4}):
+        print(f"fused overrides {np.dtype(dtype).name} {tuning}", flush=True)
+        for k, v in tuning.items():
+            ssam.ssam_set_tuning(k, v)
+        try:
+            a = dev(fld)
+            res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), coef, 4, "zero")
+            assert_parity(host(res), want, coef, 1.0, f"fused {tuning}")
+        finally:
+            for k in tuning:
+                ssam.ssam_set_tuning(k, -1)
+    a = dev(fld)
+    res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), coef, 4, "clamp")
+    assert_parity(host(res), oracle.iterate(fld, coef, 4, "clamp"), coef, 1.0, "clamp stays on single sweeps")
 
 
 def test_results_are_bitwise_reproducible(ssam):
