@@ -53,6 +53,9 @@ MEASURED_TRAFFIC_BYTES = {
     "c4_3d_star_r1_f64": 2436739858,
     "c4_3d_box_r1_f64": 2379723841,
     "c4_3d_faces_edges_f64": 2382340545,
+    "c4_3d_star_r1_f64:double_r111_b1_v2p4f1nt2_fused2": 2319630654,
+    "c4_3d_box_r1_f64:double_r111_b3_v2p4f1nt2_fused2": 2511855644,
+    "c4_3d_faces_edges_f64:double_r111_b2_v2p4f0nt2_fused2": 2252243892,
     "c5_3d_star_r4_f32": 1248362483,
     "c5_3d_star_r4_f64": 2444633941,
 }
@@ -236,12 +239,14 @@ def main() -> int:
         ms = float(np.mean([s.elapsed_time(e) for s, e in ev[c.name]]))
         # a launch is one sweep, or several where ssam_stencil_iterate fuses 2D sweeps: such a
         # launch still reads and writes the grid once, and does the arithmetic of all its sweeps
-        kind = "iterate2d" if (c.kind == "stencil2d" and c.steps > 1) else c.kind
+        kind = c.kind if c.steps == 1 else {"stencil2d": "iterate2d", "stencil3d": "iterate3d"}[c.kind]
         kname = ssam.ssam_describe(kind, c.shape, case_coef(c), c.boundary).split()[0]
         launches, t = 0, 0
         while t < c.steps:   # replay the planner: a "..._fusedS" launch performs S sweeps
-            nm = ssam.ssam_describe(kind, c.shape, case_coef(c), c.boundary, remaining=c.steps - t).split()[0] \
-                if kind == "iterate2d" else kname
+            if kind == "iterate2d":
+                nm = ssam.ssam_describe(kind, c.shape, case_coef(c), c.boundary, remaining=c.steps - t).split()[0]
+            else:   # 3D: pairs of sweeps while two or more remain
+                nm = kname if c.steps - t >= 2 else ssam.ssam_describe(c.kind, c.shape, case_coef(c), c.boundary).split()[0]
             t += int(nm.rsplit("_fused", 1)[1]) if "_fused" in nm else 1
             launches += 1
         per_launch_ms = ms / launches

@@ -80,8 +80,8 @@ int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
 /* `steps` Jacobi sweeps (paper Sec. 2.2: s_{i+1} computed from s_i) with two buffers, each
  * launch reading one and writing the other; every grid point is updated each sweep, the
  * boundary rule supplying reads outside the grid.  D == 1 with rz == 0 is the 2D case.
- * A launch performs one sweep, or -- 2D, zero padding, a compiled multi-sweep instance for the
- * shape -- several sweeps with the intermediate fields held in registers (temporal blocking,
+ * A launch performs one sweep, or -- zero padding, a compiled multi-sweep instance for the
+ * shape (2D: up to 8 sweeps; 3D radius 1: 2) -- several sweeps with the intermediate fields held in registers (temporal blocking,
  * which Sec. 6.4 says the model permits); the result is the same field to rounding either way.
  * *d_result (host location, may be NULL) receives the buffer that holds the field after
  * `steps` sweeps: d_a when the number of LAUNCHES is even (steps == 0 does nothing), d_b when
@@ -110,7 +110,8 @@ int ssam_set_tuning(const char *name, int value);
  * (M, N) and the default anchor; kind 1 = ssam_stencil2d with (a, b) = (rx, ry); kind 2 =
  * ssam_stencil3d with (a, b, c) = (rx, ry, rz); kind 3 = the launch ssam_stencil_iterate uses
  * on a 2D grid with (a, b) = (rx, ry) while c sweeps remain (c <= 0: many); an instance named
- * "..._fusedS" performs S sweeps.  The tile plan follows the paper's overlapped
+ * "..._fusedS" performs S sweeps; kind 4 = the same for a 3D grid with (a, b, c) = (rx, ry, rz)
+ * while two or more sweeps remain.  The tile plan follows the paper's overlapped
  * blocking (Sec. 4.5, Sec. 4.7) re-derived for 64 lanes of V columns each. */
 int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
                   int boundary, int dtype, char *buf, int buflen);

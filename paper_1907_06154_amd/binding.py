@@ -190,7 +190,7 @@ def ssam_set_tuning(name: str, value: int) -> None:
 
 def ssam_describe(kind: str, shape, coef, boundary: str = "zero", remaining: int = 0) -> str:
     """Kernel instance and tile geometry the dispatcher picks (host only, nothing is launched).
-    kind: "conv2d" (coef [N][M]), "stencil2d", "iterate2d" or "stencil3d" (coefficient box); shape (H, W) or (D, H, W)."""
+    kind: "conv2d" (coef [N][M]), "stencil2d", "iterate2d", "stencil3d" or "iterate3d" (coefficient box); shape (H, W) or (D, H, W)."""
     coef = np.ascontiguousarray(coef)
     code = SSAM_F32 if coef.dtype == np.float32 else SSAM_F64
     buf = ctypes.create_string_buffer(512)
@@ -206,6 +206,10 @@ def ssam_describe(kind: str, shape, coef, boundary: str = "zero", remaining: int
         H, W = shape
         rx, ry, _ = _radii(coef, 2)
         st = lib().ssam_describe(3, W, H, 1, coef.ctypes.data, rx, ry, int(remaining), BOUNDARY[boundary], code, buf, 512)
+    elif kind == "iterate3d":   # the launch ssam_stencil_iterate issues on a 3D grid while >= 2 sweeps are left
+        D, H, W = shape
+        rx, ry, rz = _radii(coef, 3)
+        st = lib().ssam_describe(4, W, H, D, coef.ctypes.data, rx, ry, rz, BOUNDARY[boundary], code, buf, 512)
     elif kind == "stencil3d":
         D, H, W = shape
         rx, ry, rz = _radii(coef, 3)

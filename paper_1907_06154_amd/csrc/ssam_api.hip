@@ -259,7 +259,7 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
 }
 
 template <typename T>
-const Instance3D* pick3d(const Problem3D& p, int want_variant)
+const Instance3D* pick3d(const Problem3D& p, int want_variant, int sweeps = 1)
 {
     const T* c = static_cast<const T*>(p.c);
     int budget = tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
@@ -269,32 +269,43 @@ const Instance3D* pick3d(const Problem3D& p, int want_variant)
     const Instance3D* best = nullptr;
     for (const Instance3D& i : registry3d()) {
         if (i.dtype != p.dtype || i.rx != p.rx || i.ry != strip_r || i.rz != march_r || i.budget < budget) continue;
-        if (i.variant != want_variant) continue;
+        if (i.variant != want_variant || i.sweeps != sweeps) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
 }
 
-// Several sweeps in one launch, where the shape has a fused instance (2D, zero padding): the
-// deepest compiled one that does not exceed `max_sweeps` (the sweeps still to do) nor the
-// "fuse_sweeps" cap.  Returns the number of sweeps the launch performs, 0 when the caller should
-// run a single sweep instead.
-int run2d_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::string* name, int* rc)
+// Several sweeps in one launch, where the shape has a fused instance (zero padding; 3D only when
+// marching along z): the deepest compiled one that does not exceed `max_sweeps` (the sweeps still
+// to do) nor the "fuse_sweeps" cap.  Returns the number of sweeps the launch performs, 0 when the
+// caller should run a single sweep instead.
+int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::string* name, int* rc)
 {
     const Tuning tu = current_tuning();
-    if (tu.fuse_sweeps == 0 || tu.fuse_sweeps == 1 || tu.force_generic > 0 || p.D != 1 || p.rz != 0 ||
-        p.boundary != SSAM_BOUNDARY_ZERO)
+    if (tu.fuse_sweeps == 0 || tu.fuse_sweeps == 1 || tu.force_generic > 0 || p.boundary != SSAM_BOUNDARY_ZERO)
         return 0;
     if (tu.fuse_sweeps > 1 && tu.fuse_sweeps < max_sweeps) max_sweeps = tu.fuse_sweeps;
     if (max_sweeps > kMaxFusedSweeps) max_sweeps = kMaxFusedSweeps;
-    Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
     const int v = tu.variant > 0 ? tu.variant : 0;
+    const bool flat = p.D == 1 && p.rz == 0;
+    if (!flat && tu.march_axis == 1) return 0;
+    Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
     for (int sweeps = max_sweeps; sweeps >= 2; --sweeps) {
-        const Instance2D* inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, v, sweeps) : pick2d<double>(q, true, v, sweeps);
-        if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, sweeps) : pick2d<double>(q, true, 0, sweeps);
-        if (!inst) continue;
-        if (name) *name = inst->name;
-        *rc = inst->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        hipError_t e;
+        if (flat) {
+            const Instance2D* inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, v, sweeps) : pick2d<double>(q, true, v, sweeps);
+            if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, sweeps) : pick2d<double>(q, true, 0, sweeps);
+            if (!inst) continue;
+            if (name) *name = inst->name;
+            e = inst->launch(q, tu, geo, dry);
+        } else {
+            const Instance3D* inst = p.dtype == SSAM_F32 ? pick3d<float>(p, v, sweeps) : pick3d<double>(p, v, sweeps);
+            if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p, 0, sweeps) : pick3d<double>(p, 0, sweeps);
+            if (!inst) continue;
+            if (name) *name = inst->name;
+            e = inst->launch(p, tu, geo, dry);
+        }
+        *rc = e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
         return sweeps;
     }
     return 0;
@@ -417,7 +428,7 @@ int ssam_stencil_iterate(void* d_a, void* d_b, int W, int H, int D, const void* 
     for (int t = 0; t < steps;) {
         Problem3D p{src, dst, W, H, D, h_coef, rx, ry, rz, boundary, dtype, (hipStream_t)hip_stream};
         int rc = SSAM_OK;
-        if (const int fused = run2d_fused(p, steps - t, nullptr, false, nullptr, &rc)) {
+        if (const int fused = run_fused(p, steps - t, nullptr, false, nullptr, &rc)) {
             if (rc) return rc;
             t += fused;
         } else {
@@ -508,7 +519,18 @@ int ssam_describe(int kind, int W, int H, int D, const void* h_coef, int a, int 
         if (a < 0 || b < 0 || a > SSAM_MAX_RADIUS || b > SSAM_MAX_RADIUS) return SSAM_ERR_SHAPE;
         Problem3D p{nullptr, out, W, H, 1, h_coef, a, b, 0, boundary, dtype, nullptr};
         int rc = SSAM_OK;
-        if (run2d_fused(p, c > 0 ? c : kMaxFusedSweeps, &g, true, &name, &rc)) return describe(rc, name, g, buf, buflen);
+        if (run_fused(p, c > 0 ? c : kMaxFusedSweeps, &g, true, &name, &rc)) return describe(rc, name, g, buf, buflen);
+        return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
+    }
+    if (kind == 4) {   // the launch ssam_stencil_iterate uses on a 3D grid while two or more sweeps remain
+        if (!h_coef) return SSAM_ERR_NULL;
+        if (int e = check_enums(boundary, dtype)) return e;
+        if (int e = check_dims(W, H, D)) return e;
+        if (a < 0 || b < 0 || c < 0 || a > SSAM_MAX_RADIUS || b > SSAM_MAX_RADIUS || c > SSAM_MAX_RADIUS)
+            return SSAM_ERR_SHAPE;
+        Problem3D p{nullptr, out, W, H, D, h_coef, a, b, c, boundary, dtype, nullptr};
+        int rc = SSAM_OK;
+        if (run_fused(p, kMaxFusedSweeps, &g, true, &name, &rc)) return describe(rc, name, g, buf, buflen);
         return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
     }
     return SSAM_ERR_ENUM;

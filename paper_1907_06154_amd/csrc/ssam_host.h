@@ -77,6 +77,7 @@ struct Instance3D {
     int dtype, rx, ry, rz, budget;  // budget = max number of non-zero offset components (1 star, 2, 3 box)
     int variant;
     Launch3DFn launch;
+    int sweeps = 1;                 // Jacobi sweeps one launch performs (2: the fused kernel, zero padding, z march only)
 };
 
 std::vector<Instance2D>& registry2d();

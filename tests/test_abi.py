@@ -161,3 +161,23 @@ def test_fused_sweep_plan(L):
             ssam.ssam_set_tuning("fuse_sweeps", -1)
     wide = np.ones((15, 15))   # radius 7: no fused instance
     assert parse(ssam.ssam_describe("iterate2d", (512, 512), wide, "zero"))[0] == "generic_direct"
+
+
+def test_fused_sweep_plan_3d(L):
+    """Radius-1 3D stencils with zero padding run two sweeps per launch when marching along z, with
+    twice the halo lanes of a single sweep; radius 4, clamp and the y march keep single sweeps."""
+    for c in wl.config4():
+        one, g1 = parse(ssam.ssam_describe("stencil3d", c.shape, c.coef, "zero"))
+        two, g2 = parse(ssam.ssam_describe("iterate3d", c.shape, c.coef, "zero"))
+        assert two.endswith("_fused2") and "_fused" not in one
+        assert g2["halo_lanes"] == 2 * g1["halo_lanes"] and g2["valid_lanes"] <= 64 - g2["halo_lanes"]
+        assert g2["tiles"] == g2["strips_x"] * g2["tiles_y"] * g2["tiles_z"]
+        assert parse(ssam.ssam_describe("iterate3d", c.shape, c.coef, "clamp"))[0] == \
+            parse(ssam.ssam_describe("stencil3d", c.shape, c.coef, "clamp"))[0]
+        ssam.ssam_set_tuning("march_axis", 1)
+        try:
+            assert "_fused" not in ssam.ssam_describe("iterate3d", c.shape, c.coef, "zero")
+        finally:
+            ssam.ssam_set_tuning("march_axis", -1)
+    for c in wl.config5():
+        assert "_fused" not in ssam.ssam_describe("iterate3d", c.shape, c.coef, "zero")

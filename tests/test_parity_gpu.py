@@ -192,7 +192,7 @@ def planned_launches(ssam, shape, coef, steps, boundary):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
-@pytest.mark.parametrize("kind,r", [("box", 1), ("star", 1), ("box", 2), ("star", 2), ("star", 3), ("star", 4)])
+@pytest.mark.parametrize("kind,r", [("box", 1), ("star", 1), ("box", 2), ("star", 2), ("star", 3), ("star", 4), ("star", 5), ("star", 6)])
 def test_fused_sweeps_match_oracle(ssam, dtype, kind, r):
     """Several 2D sweeps run as one launch (zero padding): every step count and fusion depth, grids
     smaller than a tile, ragged tails, rows that are not vector-aligned; and fusion switched off."""
@@ -238,6 +238,42 @@ def test_fused_sweeps_tile_overrides_and_clamp(ssam, dtype):
     a = dev(fld)
     res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), coef, 4, "clamp")
     assert_parity(host(res), oracle.iterate(fld, coef, 4, "clamp"), coef, 1.0, "clamp stays on single sweeps")
+
+
+FUSED_SHAPES_3D = [(1, 1, 1), (3, 5, 7), (9, 33, 130), (20, 13, 140), (70, 10, 224), (17, 40, 300)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["star", "faces_edges", "box"])
+def test_fused_sweeps_3d_match_oracle(ssam, dtype, kind):
+    """Radius-1 3D stencils run two sweeps per launch (zero padding, march along z): odd and even step
+    counts, grids smaller than a tile, ragged tails, unaligned rows, every compiled variant."""
+    mask = {"star": wl.mask_star(1, 1, 1), "box": wl.mask_box(1, 1, 1), "faces_edges": wl.mask_faces_edges()}[kind]
+    coef = wl.seeded_coefficients(mask, 850, dtype)
+    # the fp32 27-point box has no two-sweep instance (it measured no faster than single sweeps)
+    has_fused = not (kind == "box" and dtype == np.float32)
+    assert ssam.ssam_describe("iterate3d", (64, 64, 64), coef, "zero").split()[0].endswith("_fused2") == has_fused
+    assert "_fused" not in ssam.ssam_describe("iterate3d", (64, 64, 64), coef, "clamp")
+    for shape in FUSED_SHAPES_3D:
+        fld = wl.uniform_field(shape, -1.0, 1.0, 860 + shape[0], dtype)
+        for steps in (2, 3, 4, 5):
+            want = oracle.iterate(fld, coef, steps, "zero")
+            for tuning in ({}, {"fuse_sweeps": 0}, {"variant": 1},
+                           {"planes_per_wave": 3}, {"valid_lanes": 9, "planes_per_wave": 5}, {"march_axis": 1}):
+                print(f"fused3d {np.dtype(dtype).name} {kind} {shape} steps {steps} {tuning}", flush=True)
+                for k, v in tuning.items():
+                    ssam.ssam_set_tuning(k, v)
+                try:
+                    fused = "_fused2" in ssam.ssam_describe("iterate3d", shape, coef, "zero")
+                    a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+                    res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
+                finally:
+                    for k in tuning:
+                        ssam.ssam_set_tuning(k, -1)
+                assert fused == (has_fused and tuning.get("fuse_sweeps") != 0 and tuning.get("march_axis") != 1)
+                launches = steps // 2 + steps % 2 if fused else steps
+                assert res.data_ptr() == (a if launches % 2 == 0 else b).data_ptr()
+                assert_parity(host(res), want, coef, 1.0, f"fused3d {kind} {shape} steps {steps} {tuning}")
 
 
 def test_results_are_bitwise_reproducible(ssam):
