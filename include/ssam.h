@@ -122,6 +122,37 @@ int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int 
  * hardware traffic counters are scaled by. */
 int ssam_probe_copy(const void *d_in, void *d_out, size_t nbytes, void *hip_stream);
 
+/* Measurement aid: cycles per operation of the primitives the kernels are built from -- the
+ * gfx950 counterpart of the latency table of the paper's performance model (Sec. 5.1, Table 2;
+ * the shuffle, multiply-add and shared-memory read of Eq. (4)-(5)).  One block of `waves` waves
+ * (1..16; more than 4 put several waves on one SIMD) runs, in every wave, `ilp` (1, 2, 4 or 8)
+ * independent chains of `chain` dependent operations each (32..2^24, rounded down to a multiple
+ * of 32) and every wave reads the shader clock and the constant-rate wall clock before and after; the
+ * time reported is the span from the first wave's start to the last wave's end.
+ * ilp = 1, waves = 1 gives the latency of one dependent operation; larger values approach the
+ * issue rate.  d_scratch: device memory, 256-byte aligned, at least SSAM_PROBE_SCRATCH_BYTES,
+ * overwritten.  h_result (host, 2 doubles): [0] shader-clock ticks per operation of one chain,
+ * [1] nanoseconds per operation.  Unlike the other entry points this one synchronises
+ * hip_stream before it returns.  Errors: SSAM_ERR_NULL, SSAM_ERR_ENUM (op), SSAM_ERR_SHAPE (ilp,
+ * waves, chain), SSAM_ERR_DIM (scratch too small or misaligned), SSAM_ERR_HIP. */
+typedef enum {
+    SSAM_PROBE_FMA_F32 = 0,       /* v_fma_f32, dependent through the multiplicand            */
+    SSAM_PROBE_FMA_F64 = 1,       /* v_fma_f64                                                */
+    SSAM_PROBE_ADD_F32 = 2,       /* v_add_f32                                                */
+    SSAM_PROBE_DPP_WAVE_SHR = 3,  /* v_mov_b32 with DPP wave_shr:1 -- the shift the kernels use */
+    SSAM_PROBE_DPP_ROW_SHR = 4,   /* v_mov_b32 with DPP row_shr:1 (within rows of 16 lanes)    */
+    SSAM_PROBE_DS_SWIZZLE = 5,    /* ds_swizzle_b32, lane ^ 1                                  */
+    SSAM_PROBE_DS_BPERMUTE = 6,   /* ds_bpermute_b32 from the lane below (a recompiled __shfl_up) */
+    SSAM_PROBE_LDS_READ = 7,      /* ds_read_b32, address from the previous read, no conflicts */
+    SSAM_PROBE_LOAD_L1 = 8,       /* global_load_dword, address from the previous load, 16 KiB footprint */
+    SSAM_PROBE_LOAD_L2 = 9,       /* the same with a 1 MiB footprint, 4 KiB between steps      */
+    SSAM_PROBE_SHIFT_F64 = 10,    /* the 64-bit lane shift of the fp64 kernels (two DPP moves)  */
+    SSAM_PROBE_OPS = 11
+} ssam_probe_op;
+#define SSAM_PROBE_SCRATCH_BYTES (2u << 20)
+int ssam_probe_latency(int op, int ilp, int waves, int chain, void *d_scratch, size_t scratch_bytes,
+                       double *h_result, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

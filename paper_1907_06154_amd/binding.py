@@ -20,7 +20,7 @@ SSAM_F32, SSAM_F64 = 0, 1
 SSAM_BOUNDARY_ZERO, SSAM_BOUNDARY_CLAMP = 0, 1
 BOUNDARY = {"zero": SSAM_BOUNDARY_ZERO, "clamp": SSAM_BOUNDARY_CLAMP}
 EXPORTS = ["ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
-           "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy"]
+           "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy", "ssam_probe_latency"]
 
 
 class SsamError(RuntimeError):
@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.ssam_set_tuning.argtypes = [ctypes.c_char_p, ci]
         L.ssam_describe.argtypes = [ci, ci, ci, ci, vp, ci, ci, ci, ci, ci, ctypes.c_char_p, ci]
         L.ssam_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.ssam_probe_latency.argtypes = [ci, ci, ci, ci, vp, ctypes.c_size_t, vp, vp]
+        L.ssam_probe_latency.restype = ci
         for name in EXPORTS:
             if name not in ("ssam_status_string",):
                 getattr(L, name).restype = ci
@@ -229,3 +231,23 @@ def ssam_probe_copy(d_in, d_out, stream=None):
         raise ValueError("d_in and d_out must have the same size in bytes")
     _check(lib().ssam_probe_copy(d_in.data_ptr(), d_out.data_ptr(), nbytes, _stream_ptr(stream)), "ssam_probe_copy")
     return d_out
+
+
+PROBE_OPS = ["fma_f32", "fma_f64", "add_f32", "dpp_wave_shr", "dpp_row_shr", "ds_swizzle", "ds_bpermute",
+             "lds_read", "load_l1", "load_l2", "shift_f64"]
+PROBE_SCRATCH_BYTES = 2 << 20
+
+
+def ssam_probe_latency(op: str, ilp: int = 1, waves: int = 1, chain: int = 1 << 15, d_scratch=None, stream=None):
+    """Cycles (shader clock) and nanoseconds per operation of one dependent chain of `op`
+    (a name from PROBE_OPS); synchronises the stream.  d_scratch: a device tensor of at least
+    PROBE_SCRATCH_BYTES bytes (allocated here when omitted)."""
+    import torch
+    if d_scratch is None:
+        d_scratch = torch.empty(PROBE_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    _device_tensor(d_scratch, "d_scratch")
+    res = (ctypes.c_double * 2)()
+    st = lib().ssam_probe_latency(PROBE_OPS.index(op), int(ilp), int(waves), int(chain), d_scratch.data_ptr(),
+                                  d_scratch.numel() * d_scratch.element_size(), res, _stream_ptr(stream))
+    _check(st, "ssam_probe_latency")
+    return float(res[0]), float(res[1])

@@ -324,3 +324,34 @@ def test_errors_are_reported_not_launched(ssam):
     with pytest.raises(ssam.SsamError) as e:
         ssam.ssam_stencil_iterate(img, torch.empty_like(img), filt, -1)
     assert e.value.status == 3
+
+
+def test_latency_probe_orders_the_primitives(ssam):
+    """The micro-benchmarks behind the latency table: every figure is positive and finite, a longer
+    chain gives the same per-operation cost, and the orderings the kernel design rests on hold --
+    a DPP lane shift costs about one VALU operation and far less than the same shift through the
+    LDS crossbar or an LDS read (Sec. 5.1 of the paper puts the warp shuffle at the cost of a
+    shared-memory read; here it is not)."""
+    from paper_1907_06154_amd.binding import PROBE_OPS
+    scratch = torch.empty(2 << 20, dtype=torch.uint8, device="cuda")
+    lat = {}
+    for op in PROBE_OPS:
+        print(f"latency probe {op}", flush=True)
+        ssam.ssam_probe_latency(op, 1, 1, 4096, scratch)
+        c1, ns1 = ssam.ssam_probe_latency(op, 1, 1, 8192, scratch)
+        c2, _ = ssam.ssam_probe_latency(op, 1, 1, 32768, scratch)
+        assert np.isfinite(c1) and np.isfinite(ns1) and c1 > 0.5 and ns1 > 0.1 and c1 < 5000
+        assert abs(c1 - c2) <= 0.15 * c2 + 1.0, (op, c1, c2)
+        lat[op] = c2
+        many, _ = ssam.ssam_probe_latency(op, 8, 4, 8192, scratch)
+        assert many / 8 <= lat[op] * 1.1 + 1.0     # independent chains overlap
+    assert lat["dpp_wave_shr"] < 3 * lat["fma_f32"]
+    assert lat["dpp_wave_shr"] < 0.5 * lat["ds_bpermute"]
+    assert lat["dpp_wave_shr"] < 0.5 * lat["lds_read"]
+    assert lat["lds_read"] < lat["load_l2"]
+    assert lat["load_l1"] <= lat["load_l2"] * 1.05
+    assert lat["shift_f64"] < 3 * lat["dpp_wave_shr"] + 4
+    with pytest.raises(ssam.SsamError):
+        ssam.ssam_probe_latency("fma_f32", 3, 1, 4096, scratch)
+    with pytest.raises(ssam.SsamError):
+        ssam.ssam_probe_latency("fma_f32", 1, 1, 4096, scratch[:1024])
