@@ -59,6 +59,35 @@ def uniform_field(shape: Tuple[int, ...], lo: float, hi: float, seed: int, dtype
     return out.reshape(shape)
 
 
+def uniform_field_on(device, shape: Tuple[int, ...], lo: float, hi: float, seed: int, dtype):
+    """uniform_field(...) computed on a torch device: the same counters, the same integer hash in
+    two's-complement int64 arithmetic and the same float64 mapping, so the bits are identical.  For
+    grids too large to generate on the host in reasonable time.  Returns a torch tensor."""
+    import torch
+    n = int(np.prod(shape))
+    tdt = {np.dtype(np.float32): torch.float32, np.dtype(np.float64): torch.float64}[np.dtype(dtype)]
+    out = torch.empty(n, dtype=tdt, device=device)
+
+    def i64(v: int) -> int:   # the uint64 constant as the int64 with the same bits
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    def lsr(z, k: int):       # logical shift right of int64 bit patterns
+        return (z >> k) & ((1 << (64 - k)) - 1)
+
+    chunk = 1 << 26
+    for start in range(0, n, chunk):
+        stop = min(n, start + chunk)
+        z = torch.arange(start, stop, dtype=torch.int64, device=device) + i64(((seed << 40) + int(_GOLDEN)) % (1 << 64))
+        z = (z ^ lsr(z, 30)) * i64(int(_MUL1))
+        z = (z ^ lsr(z, 27)) * i64(int(_MUL2))
+        z = z ^ lsr(z, 31)
+        u = lsr(z, 11).to(torch.float64) * (1.0 / 9007199254740992.0)
+        u = u * (hi - lo)      # two rounded operations, as in uniform_at (no fused multiply-add)
+        u = u + lo
+        out[start:stop] = u.to(tdt)
+    return out.reshape(shape)
+
+
 def uniform_window(full_shape: Tuple[int, ...], lo_corner: Tuple[int, ...], win_shape: Tuple[int, ...],
                    lo: float, hi: float, seed: int, dtype) -> np.ndarray:
     """The sub-block [lo_corner, lo_corner + win_shape) of uniform_field(full_shape, ...)."""

@@ -75,3 +75,18 @@ def test_oracle_and_generators_match_the_committed_lock_file():
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     assert mod.render() == open(os.path.join(here, "golden", "oracle_lock.txt")).read()
+
+
+def test_device_generator_matches_host_generator():
+    """uniform_field_on (torch integer arithmetic) reproduces uniform_field bit for bit, including
+    counters beyond 2^31 (a window of a grid of almost 2^31 elements)."""
+    torch = pytest.importorskip("torch")
+    for dt in (np.float32, np.float64):
+        for seed in (0, 5, 123456):
+            host = wl.uniform_field((37, 1001), -1.0, 1.0, seed, dt)
+            assert np.array_equal(host, wl.uniform_field_on("cpu", (37, 1001), -1.0, 1.0, seed, dt).numpy())
+    big = (3, 46340, 46340)   # flat indices up to 6.4e9
+    tail = wl.uniform_window(big, (2, 46339, 46000), (1, 1, 340), 0.0, 1.0, 9, np.float32)
+    flat0 = (2 * 46340 + 46339) * 46340 + 46000
+    z = wl.uniform_at(np.arange(flat0, flat0 + 340, dtype=np.uint64), 0.0, 1.0, 9, np.float32)
+    assert np.array_equal(tail.ravel(), z)
