@@ -47,9 +47,9 @@ MEASURED_TRAFFIC_BYTES = {
     "c3_2d_box_r1_f64": 1102485294,
     "c3_2d_box_r2_f64": 1083534618,
     "c3_2d_star_r4_f64": 1129549854,
-    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1151098980,
-    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1210095674,
-    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1254116967,
+    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109809858,
+    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120402618,
+    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150222876,
     "c4_3d_star_r1_f64": 2436739858,
     "c4_3d_box_r1_f64": 2379723841,
     "c4_3d_faces_edges_f64": 2382340545,

@@ -2,6 +2,4 @@
 #include "ssam_kernel2d_fused.h"
 
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 6, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 8, 2, 0);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 2, 6, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 2, 8, 2, 0);

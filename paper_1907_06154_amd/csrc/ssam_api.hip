@@ -206,7 +206,8 @@ size_t elem(int dtype) { return dtype == SSAM_F32 ? 4 : 8; }
 
 // ---- dispatch ---------------------------------------------------------------------------
 template <typename T>
-const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant, int sweeps = 1)
+const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_variant, int sweeps = 1,
+                         bool any_depth = false)
 {
     const T* w = static_cast<const T*>(p.w);
     int budget = 2;
@@ -219,7 +220,8 @@ const Instance2D* pick2d(const Problem2D& p, bool stencil_semantics, int want_va
         if (i.dtype != p.dtype || i.M != p.M || i.N != p.N || i.AX != p.ax) continue;
         if (i.budget < budget) continue;
         if (i.budget == 1 && p.ay != p.N / 2) continue;   // star instances assume the centre row
-        if (i.variant != want_variant || i.sweeps != sweeps) continue;
+        if (i.variant != want_variant) continue;
+        if (any_depth ? i.sweeps < 2 : i.sweeps != sweeps) continue;
         if (!best || i.budget < best->budget) best = &i;
     }
     return best;
@@ -290,12 +292,21 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
     const bool flat = p.D == 1 && p.rz == 0;
     if (!flat && tu.march_axis == 1) return 0;
     Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
+    // the tightest tap shape any multi-sweep instance offers for this stencil: a deeper instance of a
+    // wider shape (a box standing in for a star) is not taken over a shallower one of the exact shape
+    int shape_budget = 0;
+    if (flat) {
+        const Instance2D* tight = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, 0, true) : pick2d<double>(q, true, 0, 0, true);
+        if (!tight) return 0;
+        shape_budget = tight->budget;
+    }
     for (int sweeps = max_sweeps; sweeps >= 2; --sweeps) {
         hipError_t e;
         if (flat) {
             const Instance2D* inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, v, sweeps) : pick2d<double>(q, true, v, sweeps);
-            if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, sweeps) : pick2d<double>(q, true, 0, sweeps);
-            if (!inst) continue;
+            if ((!inst || inst->budget != shape_budget) && v != 0)
+                inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, 0, sweeps) : pick2d<double>(q, true, 0, sweeps);
+            if (!inst || inst->budget != shape_budget) continue;
             if (name) *name = inst->name;
             e = inst->launch(q, tu, geo, dry);
         } else {

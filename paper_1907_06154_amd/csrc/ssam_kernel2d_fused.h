@@ -5,9 +5,9 @@
 // The march of ssam2d_kernel is run S times, back to back, inside the wave: the P rows sweep k
 // produces for a group never leave the registers -- they join the 2R rows of sweep k kept from
 // the previous group and form the window of sweep k+1.  HBM sees one read and one write per S
-// sweeps.  The price is a wider overlap between tiles: sweep k is valid on 64 - 2(k+1)*ceil(R/V)
-// lanes, so the wave stores 64 - 2S*ceil(R/V) of them, and each tile spends ceil(2(S-1)R/P)
-// extra groups at its top producing the intermediate rows its first outputs need.
+// sweeps.  The price is a wider overlap between tiles: every sweep invalidates R more columns at
+// each end of the wave, so the wave stores 64 - 2*ceil(S*R/V) lanes, and each tile spends
+// ceil(2(S-1)R/P) extra groups at its top producing the intermediate rows its first outputs need.
 //
 // Zero padding only: an intermediate value at a position outside the grid must read as 0 for
 // the next sweep, which a mask does; under the clamp rule it would be the value of another
@@ -24,8 +24,9 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
     constexpr int R = Mask::kAY;          // rows above the centre
     constexpr int KEEP = N - 1;
     static_assert(S >= 2 && N == 2 * R + 1 && Mask::kLeft == Mask::kRight, "fused sweeps need a centred stencil");
-    constexpr int H1 = (Mask::kLeft + V - 1) / V;   // halo lanes of one sweep, each side
-    constexpr int HL = S * H1, HR = S * H1;
+    // after S sweeps the S*RX outermost columns of the wave are incomplete (validity is per
+    // column, not per lane: a lane's inner columns find their neighbours in the same lane)
+    constexpr int HL = (S * Mask::kLeft + V - 1) / V, HR = HL;
     constexpr int WARM = (2 * (S - 1) * R + P - 1) / P;   // groups run before the first output group
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -178,14 +179,24 @@ template <typename T, int V, int P, class Mask, int S, int NT>
 hipError_t launch2d_fused(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     constexpr int M = Mask::kM, N = Mask::kN;
-    constexpr int H1 = (Mask::kLeft + V - 1) / V;
-    static_assert(64 - 2 * S * H1 >= 8, "stencil too wide for this many sweeps in one wave");
+    constexpr int HL = (S * Mask::kLeft + V - 1) / V;
+    static_assert(64 - 2 * HL >= 8, "stencil too wide for this many sweeps in one wave");
     if (pr.boundary != SSAM_BOUNDARY_ZERO) return hipErrorInvalidValue;
     Geometry g;
-    plan_strips(pr.W, V, S * H1, S * H1, tu.valid_lanes, &g, true);
+    plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g, true);
     g.P = P;
-    // taller tiles than the one-sweep kernel: each tile re-does the warm-up rows at its top
-    int rows = tu.rows_per_wave > 0 ? tu.rows_per_wave : (S >= 6 ? 128 : 64);   // measured on 8192^2
+    // The deep instances are arithmetic-bound: every wave takes about the same time, so the tile
+    // count should fill the machine's wave slots a whole number of times; tiles at least 8 groups
+    // tall keep the warm-up groups at each tile's top a small part of the work.
+    int rows;
+    if (tu.rows_per_wave > 0) {
+        rows = tu.rows_per_wave;
+    } else if (S >= 3) {
+        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_fused_kernel<T, V, P, Mask, S, NT>));
+        rows = balanced_rows(pr.H, P, g.strips_x, slots, 8 * P);
+    } else {
+        rows = 64;
+    }
     rows = ceil_div(rows, P) * P;
     if (rows > ceil_div(pr.H, P) * P) rows = ceil_div(pr.H, P) * P;
     g.rows_per_wave = rows;

@@ -6,7 +6,7 @@
 // on a strip widened by RY rows on each side: every loaded input plane (P + 4*RY rows) is added
 // into 2*RZ+1 in-flight first-sweep planes of P + 2*RY rows.  The first-sweep plane that completes
 // is not stored: it is the "input plane" of level 2, the ordinary march over P rows, whose
-// completed plane is stored.  HBM sees one read and one write per two sweeps.  Overlap: 2*ceil(RX/V)
+// completed plane is stored.  HBM sees one read and one write per two sweeps.  Overlap: ceil(2*RX/V)
 // halo lanes per side, 2*RY halo rows per side of the strip, 4*RZ extra planes per z-chunk.
 //
 // Zero padding only: first-sweep values at positions outside the grid are forced to 0 by a
@@ -23,8 +23,7 @@ __global__ __launch_bounds__(kBlock) void ssam3d_fused_kernel(
     constexpr int NZ = 2 * RZ + 1;
     constexpr int P1 = P + 2 * RY;      // rows of a first-sweep plane
     constexpr int C0 = P1 + 2 * RY;     // rows of an input plane
-    constexpr int H1 = (RX + V - 1) / V;
-    constexpr int HL = 2 * H1;
+    constexpr int HL = (2 * RX + V - 1) / V;   // two sweeps leave 2*RX incomplete columns at each end of the wave
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -168,10 +167,10 @@ template <typename T, int V, int P, int RX, int RY, int RZ, int BUDGET, int NT, 
 hipError_t launch3d_fused(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     typedef SliceMask<RX, RY, RZ, BUDGET, 0> Mask0;
-    constexpr int H1 = (RX + V - 1) / V;
+    constexpr int HL = (2 * RX + V - 1) / V;
     if (pr.boundary != SSAM_BOUNDARY_ZERO || pr.march_y) return hipErrorInvalidValue;
     Geometry g;
-    plan_strips(pr.W, V, 2 * H1, 2 * H1, tu.valid_lanes, &g);
+    plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g);
     g.P = P;
     g.rows_per_wave = P;
     g.tiles_y = ceil_div(pr.H, P);

@@ -47,6 +47,17 @@ def main(argv) -> int:
             else:
                 ssam.ssam_stencil_iterate(a, b, coef, sweeps, c.boundary)
 
+        # bring the clocks up before the first figure: a short run after idling reads low
+        t_end = torch.cuda.Event(enable_timing=True)
+        t_beg = torch.cuda.Event(enable_timing=True)
+        t_beg.record()
+        while True:
+            for _ in range(5):
+                run()
+            t_end.record()
+            torch.cuda.synchronize()
+            if t_beg.elapsed_time(t_end) > 300.0:
+                break
         for combo in itertools.product(*vals):
             for k, v in zip(keys, combo):
                 ssam.ssam_set_tuning(k, v)

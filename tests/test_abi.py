@@ -133,7 +133,7 @@ def test_shape_classification(L):
 
 def test_fused_sweep_plan(L):
     """2D sweeps with zero padding run several to a launch; the overlap grows with the depth S on
-    every side (S times the single-sweep halo); clamp and shapes without a fused instance keep
+    every side (S*r incomplete columns); clamp and shapes without a fused instance keep
     single sweeps; the planner never runs more sweeps than remain."""
     import re
     for c in wl.config3():
@@ -145,7 +145,7 @@ def test_fused_sweep_plan(L):
             many, g = parse(ssam.ssam_describe("iterate2d", c.shape, coef, "zero", remaining=remaining))
             S = int(re.search(r"_fused(\d+)$", many).group(1))
             assert 2 <= S and (remaining == 0 or S <= remaining)
-            assert g["halo_lanes"] == S * g1["halo_lanes"] == 2 * S * -(-r // g["V"])
+            assert g["halo_lanes"] == 2 * -(-S * r // g["V"])   # S*r incomplete columns per side
             assert g["valid_lanes"] <= 64 - g["halo_lanes"]
             assert g["strips_x"] * g["valid_lanes"] * g["V"] >= c.shape[1]
             assert g["rows_per_wave"] % g["P"] == 0
@@ -165,12 +165,12 @@ def test_fused_sweep_plan(L):
 
 def test_fused_sweep_plan_3d(L):
     """Radius-1 3D stencils with zero padding run two sweeps per launch when marching along z, with
-    twice the halo lanes of a single sweep; radius 4, clamp and the y march keep single sweeps."""
+    two incomplete columns per side; radius 4, clamp and the y march keep single sweeps."""
     for c in wl.config4():
         one, g1 = parse(ssam.ssam_describe("stencil3d", c.shape, c.coef, "zero"))
         two, g2 = parse(ssam.ssam_describe("iterate3d", c.shape, c.coef, "zero"))
         assert two.endswith("_fused2") and "_fused" not in one
-        assert g2["halo_lanes"] == 2 * g1["halo_lanes"] and g2["valid_lanes"] <= 64 - g2["halo_lanes"]
+        assert g2["halo_lanes"] == 2 * -(-2 * 1 // g2["V"]) and g2["valid_lanes"] <= 64 - g2["halo_lanes"]
         assert g2["tiles"] == g2["strips_x"] * g2["tiles_y"] * g2["tiles_z"]
         assert parse(ssam.ssam_describe("iterate3d", c.shape, c.coef, "clamp"))[0] == \
             parse(ssam.ssam_describe("stencil3d", c.shape, c.coef, "clamp"))[0]
