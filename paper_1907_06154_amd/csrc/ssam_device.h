@@ -250,8 +250,11 @@ struct RowPair {                // HEAD rows kept from the previous window, then
 // Products of one filter column, for all P window positions: the lane's own column i = j + COL
 // multiplies filter column AX + DX and accumulates into the partial sum of output column j.
 // (Sec. 4.3: an N-term inner product between a register vector and a filter column.)
+// set[j] says whether the sums of output column j hold a value yet: the first product is a plain
+// multiplication, so no sum is ever zero-initialised.  All indices are compile-time constants
+// after unrolling, and so are the flags.
 template <typename T, int V, int P, class Mask, int DX, int COL, bool PIN, bool SKIP_ANCHOR, class Rows>
-__device__ __forceinline__ void column_products(const Rows& r, ConstPtr<T> w, T (&s)[P][V])
+__device__ __forceinline__ void column_products(const Rows& r, ConstPtr<T> w, T (&s)[P][V], bool (&set)[V])
 {
     constexpr int N = Mask::kN, AX = Mask::kAX;
     const int z = PIN ? opaque_zero() : 0;
@@ -263,28 +266,18 @@ __device__ __forceinline__ void column_products(const Rows& r, ConstPtr<T> w, T 
             for (int j = 0; j < V; ++j) {
                 const int i = j + COL;
                 if (i >= 0 && i < V) {
+                    if (set[j]) {
 #pragma unroll
-                    for (int p = 0; p < P; ++p) s[p][j] = fma_t(r.at(p + n, i), wv, s[p][j]);
+                        for (int p = 0; p < P; ++p) s[p][j] = fma_t(r.at(p + n, i), wv, s[p][j]);
+                    } else {
+#pragma unroll
+                        for (int p = 0; p < P; ++p) s[p][j] = r.at(p + n, i) * wv;
+                        set[j] = true;
+                    }
                 }
             }
         }
     }
-}
-
-// Has the partial sum of output column j received any product by the time it leaves the lane
-// at distance d from its owner?  (side -1: the chain coming from the left, whose taps lie
-// `reach` columns to the left at most; +1: from the right.)  Sums that are still exactly zero
-// are not shifted: with V columns per lane only the outputs near the lane's edge depend on
-// the neighbouring lane when the filter is narrow (Sec. 5.4: fewer horizontal transfers).
-template <int V>
-__host__ __device__ constexpr bool chain_touches(int j, int d, int dmax, int reach, int side)
-{
-    for (int dd = d; dd <= dmax; ++dd)
-        for (int i = 0; i < V; ++i) {
-            const int dx = side < 0 ? i - j - dd * V : i - j + dd * V;
-            if (side < 0 ? (dx >= -reach && dx <= -1) : (dx >= 1 && dx <= reach)) return true;
-        }
-    return false;
 }
 
 // For P window positions p (the sliding window of Sec. 4.2) computes
@@ -300,7 +293,11 @@ __host__ __device__ constexpr bool chain_touches(int j, int d, int dmax, int rea
 // (towards higher lane ids); taps right of the anchor travel down-lane.  At distance d from
 // the owner a lane adds the products of its own columns that fall inside the filter
 // footprint, then hands the V partial sums on (Sec. 4.4).  After ceil(kLeft/V) +
-// ceil(kRight/V) shifts the owner adds the columns it holds itself.  Lanes nearer than
+// ceil(kRight/V) shifts the owner adds the columns it holds itself.  A sum that has received no
+// product yet is not shifted, and the first product of every sum is a plain multiplication: with V
+// columns per lane only the outputs near the lane's edge depend on the neighbouring lane when the
+// filter is narrow (Sec. 5.4: fewer horizontal transfers), so for a radius-1 stencil each chain
+// carries one of the V sums and the two chains never meet.  Lanes nearer than
 // ceil(kLeft/V) to the low end of the wave, or ceil(kRight/V) to the high end, end with
 // incomplete sums: they are the overlapped-blocking halo (Sec. 4.5).
 template <typename T, int V, int P, class Mask, bool ACCUMULATE, class Rows>
@@ -314,7 +311,9 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
     constexpr bool PIN = Mask::kNW > 64;   // small coefficient sets stay resident in scalar registers
 
     T sum[P][V];
-    bool have = ACCUMULATE;   // folds to a constant: does `sum` hold a value yet
+    bool have[V];   // per output column: does `sum` hold a value yet (folds to constants)
+#pragma unroll
+    for (int j = 0; j < V; ++j) have[j] = ACCUMULATE;
     if constexpr (ACCUMULATE) {
         // the anchor tap (every mask has it) seeds the sums from `in` with a three-address FMA
         const T wa = w[Mask::widx(Mask::kAY, Mask::kAX)];
@@ -327,78 +326,70 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
     // chain arriving from the left (lower lane ids)
     if constexpr (DL > 0) {
         T s[P][V];
+        bool got[V];
 #pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < V; ++j) s[p][j] = T(0);
+        for (int j = 0; j < V; ++j) got[j] = false;
         static_for<DL>([&](auto dc) __attribute__((always_inline)) {
             constexpr int d = DL - decltype(dc)::value;            // DL, DL-1, ..., 1
             // columns of this lane relative to an output column d lanes up: dx = i - j - d*V
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) - d * V;
                 if constexpr (dx >= -Mask::kLeft && dx <= -1)
-                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, false, Rows>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx + d * V, PIN, false, Rows>(r, w, s, got);
             });
 #pragma unroll
-            for (int p = 0; p < P; ++p)
+            for (int j = 0; j < V; ++j)
+                if (got[j]) {
 #pragma unroll
-                for (int j = 0; j < V; ++j)
-                    if (chain_touches<V>(j, d, DL, Mask::kLeft, -1)) s[p][j] = shift_up(s[p][j]);
+                    for (int p = 0; p < P; ++p) s[p][j] = shift_up(s[p][j]);
+                }
         });
 #pragma unroll
-        for (int p = 0; p < P; ++p)
+        for (int j = 0; j < V; ++j)
+            if (got[j]) {
 #pragma unroll
-            for (int j = 0; j < V; ++j) {
-                if (chain_touches<V>(j, 1, DL, Mask::kLeft, -1)) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
-                else if (!have) sum[p][j] = T(0);
+                for (int p = 0; p < P; ++p) sum[p][j] = have[j] ? sum[p][j] + s[p][j] : s[p][j];
+                have[j] = true;
             }
-        have = true;
     }
     // chain arriving from the right (higher lane ids)
     if constexpr (DR > 0) {
         T s[P][V];
+        bool got[V];
 #pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < V; ++j) s[p][j] = T(0);
+        for (int j = 0; j < V; ++j) got[j] = false;
         static_for<DR>([&](auto dc) __attribute__((always_inline)) {
             constexpr int d = DR - decltype(dc)::value;
             static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
                 constexpr int dx = decltype(cc)::value - (V - 1) + d * V;
                 if constexpr (dx >= 1 && dx <= Mask::kRight)
-                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, false, Rows>(r, w, s);
+                    column_products<T, V, P, Mask, dx, dx - d * V, PIN, false, Rows>(r, w, s, got);
             });
 #pragma unroll
-            for (int p = 0; p < P; ++p)
+            for (int j = 0; j < V; ++j)
+                if (got[j]) {
 #pragma unroll
-                for (int j = 0; j < V; ++j)
-                    if (chain_touches<V>(j, d, DR, Mask::kRight, +1)) s[p][j] = shift_down(s[p][j]);
+                    for (int p = 0; p < P; ++p) s[p][j] = shift_down(s[p][j]);
+                }
         });
 #pragma unroll
-        for (int p = 0; p < P; ++p)
+        for (int j = 0; j < V; ++j)
+            if (got[j]) {
 #pragma unroll
-            for (int j = 0; j < V; ++j) {
-                if (chain_touches<V>(j, 1, DR, Mask::kRight, +1)) sum[p][j] = have ? sum[p][j] + s[p][j] : s[p][j];
-                else if (!have) sum[p][j] = T(0);
+                for (int p = 0; p < P; ++p) sum[p][j] = have[j] ? sum[p][j] + s[p][j] : s[p][j];
+                have[j] = true;
             }
-        have = true;
-    }
-    if (!have) {
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[p][j] = T(0);
     }
     // the owner's own columns: dx = i - j
     static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
         constexpr int dx = decltype(cc)::value - (V - 1);
         if constexpr (dx >= -Mask::kLeft && dx <= Mask::kRight)
-            column_products<T, V, P, Mask, dx, dx, PIN, ACCUMULATE, Rows>(r, w, sum);
+            column_products<T, V, P, Mask, dx, dx, PIN, ACCUMULATE, Rows>(r, w, sum, have);
     });
 #pragma unroll
     for (int p = 0; p < P; ++p)
 #pragma unroll
-        for (int j = 0; j < V; ++j) out[p][j] = sum[p][j];
+        for (int j = 0; j < V; ++j) out[p][j] = have[j] ? sum[p][j] : T(0);
 }
 
 // Map the hardware block id to a logical one so that consecutive logical blocks (which
