@@ -99,7 +99,10 @@ const char *ssam_status_string(int status);
  * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
  * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant" (an alternative
  * compiled instance of the same shape, where one exists), "march_axis" (3D: 0 = march along z,
- * 1 = march along y), "fuse_sweeps" (ssam_stencil_iterate: 0 or 1 = always one sweep per launch, n >= 2 = at most n).
+ * 1 = march along y), "fuse_sweeps" (ssam_stencil_iterate: 0 or 1 = always one sweep per launch, n >= 2 = at most n),
+ * "embed_waste" (a 2D filter shape without a compiled instance runs inside the smallest compiled
+ * square box that holds it, zero-padded; a value n >= 0 allows that only while the box has at most
+ * n times its taps, 0 = never: such shapes then use the direct one-point-per-thread kernel).
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 

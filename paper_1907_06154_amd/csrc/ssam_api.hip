@@ -26,7 +26,7 @@ namespace {
 
 constexpr int kMaxFusedSweeps = 8;
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
-    g_force_generic{-1}, g_variant{-1}, g_march_axis{-1}, g_fuse_sweeps{-1};
+    g_force_generic{-1}, g_variant{-1}, g_march_axis{-1}, g_fuse_sweeps{-1}, g_embed_waste{-1};
 
 Tuning current_tuning()
 {
@@ -39,6 +39,7 @@ Tuning current_tuning()
     t.variant = g_variant.load();
     t.march_axis = g_march_axis.load();
     t.fuse_sweeps = g_fuse_sweeps.load();
+    t.embed_waste = g_embed_waste.load();
     return t;
 }
 
@@ -241,6 +242,36 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
     if (inst) {
         if (name) *name = inst->name;
         return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    }
+    // No instance of this exact shape (a non-square filter, an anchor off the centre, unequal
+    // radii): embed it in the smallest compiled square box whose centre anchor leaves enough room
+    // on every side.  The added zero weights cost arithmetic, but even a 1x20 filter inside the 20x20
+    // box measured faster than the direct kernel, so there is no limit unless "embed_waste" sets one.
+    if (tu.force_generic <= 0) {
+        const int need_lo = p.ax > p.ay ? p.ax : p.ay;
+        const int hi_x = p.M - 1 - p.ax, hi_y = p.N - 1 - p.ay;
+        const int need_hi = hi_x > hi_y ? hi_x : hi_y;
+        const Instance2D* box = nullptr;
+        for (const Instance2D& i : registry2d()) {
+            if (i.dtype != p.dtype || i.M != i.N || i.budget != 2 || i.variant != 0 || i.sweeps != 1) continue;
+            if (i.AX != i.M / 2 || i.M / 2 < need_lo || i.M - 1 - i.M / 2 < need_hi) continue;
+            if (!box || i.M < box->M) box = &i;
+        }
+        if (box && (tu.embed_waste < 0 || box->M * box->N <= tu.embed_waste * p.M * p.N)) {
+            const int K = box->M, c = K / 2;
+            const size_t es = elem(p.dtype);
+            std::vector<char> padded((size_t)K * K * es, 0);
+            const char* src = static_cast<const char*>(p.w);
+            for (int n = 0; n < p.N; ++n)
+                memcpy(&padded[((size_t)(n + c - p.ay) * K + (c - p.ax)) * es], src + (size_t)n * p.M * es,
+                       (size_t)p.M * es);
+            Problem2D q = p;
+            q.M = q.N = K;
+            q.ax = q.ay = c;
+            q.w = padded.data();
+            if (name) *name = std::string(box->name) + "+embedded";
+            return box->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;   // weights are copied into the launch arguments
+        }
     }
     if (name) *name = "generic_direct";
     if (geo) {
@@ -492,6 +523,7 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "variant")) g_variant = value;
     else if (!strcmp(name, "march_axis")) g_march_axis = value;
     else if (!strcmp(name, "fuse_sweeps")) g_fuse_sweeps = value;
+    else if (!strcmp(name, "embed_waste")) g_embed_waste = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

@@ -22,6 +22,7 @@ struct Tuning {
     int force_generic = -1;    // 1: skip the compiled instances, use the direct kernel
     int variant = -1;          // pick an alternative compiled instance of the same shape
     int march_axis = -1;       // 3D: 0 march along z (strip along y), 1 march along y (strip along z)
+    int embed_waste = -1;      // largest box-to-filter tap ratio for embedding an odd shape in a compiled box (0: never)
     int fuse_sweeps = -1;      // iteration: 0 = one sweep per launch, otherwise two where a fused instance exists
 };
 

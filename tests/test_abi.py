@@ -119,9 +119,23 @@ def test_shape_classification(L):
         coef = c.coef if c.kind == "stencil3d" else c.coef[0]
         name, g = parse(ssam.ssam_describe(c.kind, c.shape, coef, c.boundary))
         assert name.startswith(prefix), (nm, name)
-    # a shape without a compiled instance falls to the direct kernel instead of failing
-    name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 7), dtype=np.float32), "zero"))
+    # a shape without a compiled instance runs inside the smallest compiled square box that holds it ...
+    name, g = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 7), dtype=np.float32), "zero"))
+    assert name == "float_M7N7_b2_v4p8f1nt2+embedded" and g["halo_lanes"] == 2
+    name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((1, 6), dtype=np.float32), "zero"))
+    assert name.startswith("float_M6N6_b2") and name.endswith("+embedded")
+    # ... one-dimensional filters of odd length have instances of their own ...
+    name, g = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((7, 1), dtype=np.float32), "zero"))
+    assert name.startswith("float_M1N7_b2") and g["halo_lanes"] == 0
+    # ... and what no box holds (wider than 20, or embedding switched off) falls to the direct kernel
+    name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 23), dtype=np.float32), "zero"))
     assert name == "generic_direct"
+    ssam.ssam_set_tuning("embed_waste", 0)
+    try:
+        name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 7), dtype=np.float32), "zero"))
+        assert name == "generic_direct"
+    finally:
+        ssam.ssam_set_tuning("embed_waste", -1)
     # a dense 3D box too large for the argument block is refused
     with pytest.raises(ssam.SsamError):
         ssam.ssam_describe("stencil3d", (32, 32, 32), np.ones((9, 9, 9), dtype=np.float64), "zero")

@@ -21,7 +21,8 @@ def ssam():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     s.lib()   # raises if the HIP library is missing: there is no fallback
     yield s
-    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant", "march_axis"):
+    for name in ("rows_per_wave", "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant", "march_axis",
+                 "fuse_sweeps", "embed_waste"):
         s.ssam_set_tuning(name, -1)
 
 
@@ -48,6 +49,38 @@ def test_conv2d_f32(ssam, MN, boundary):
         got = host(ssam.ssam_conv2d(dev(img), filt, boundary))
         want = oracle.conv2d(img, filt, boundary)
         assert_parity(got, want, filt, 1.0, f"conv {M}x{N} {boundary} {H}x{W}")
+
+
+@pytest.mark.parametrize("MN", [(5, 7), (7, 5), (1, 4), (4, 1), (1, 15), (15, 1), (1, 20), (20, 1), (2, 16), (7, 13), (13, 1)])
+def test_odd_filter_shapes_and_anchors_f32(ssam, MN):
+    """Filters without an instance of their own shape -- non-square, one-dimensional, anchored off the
+    centre -- run embedded in a compiled square box (or on a 1D instance); same tolerance."""
+    M, N = MN
+    filt = wl.seeded_filter(M, N, 500 + 32 * M + N, np.float32)
+    anchors = [None, (0, 0), (M - 1, N - 1), (M // 3, (2 * N) // 3)]
+    for k, (H, W) in enumerate([(70, 300), (37, 259), (3, 2050), (1, 1000), (1000, 1)]):
+        img = wl.uniform_field((H, W), 0.0, 1.0, 510 + k, np.float32)
+        for anchor in anchors:
+            for boundary in ("clamp", "zero"):
+                print(f"odd filter {M}x{N} anchor {anchor} {boundary} grid {H}x{W}", flush=True)
+                got = host(ssam.ssam_conv2d(dev(img), filt, boundary, anchor))
+                assert_parity(got, oracle.conv2d(img, filt, boundary, anchor), filt, 1.0, f"odd {M}x{N} {anchor} {boundary}")
+    name = ssam.ssam_describe("conv2d", (70, 300), filt, "clamp").split()[0]
+    assert name != "generic_direct"
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_anisotropic_stencils_are_embedded(ssam, dtype):
+    for rx, ry in ((3, 1), (1, 2), (0, 2), (4, 0)):
+        coef = wl.seeded_coefficients(wl.mask_box(rx, ry), 520 + rx, dtype)[0]
+        fld = wl.uniform_field((70, 300), -1.0, 1.0, 521, dtype)
+        assert ssam.ssam_describe("stencil2d", (70, 300), coef, "zero").split()[0] != "generic_direct"
+        for boundary in ("clamp", "zero"):
+            print(f"anisotropic {np.dtype(dtype).name} rx{rx} ry{ry} {boundary}", flush=True)
+            got = host(ssam.ssam_stencil2d(dev(fld), coef, boundary))
+            assert_parity(got, oracle.stencil(fld, coef, boundary), coef, 1.0, f"aniso {rx} {ry} {boundary}")
+        res = ssam.ssam_stencil_iterate(dev(fld), torch.empty_like(dev(fld)), coef, 3, "zero")
+        assert_parity(host(res), oracle.iterate(fld, coef, 3, "zero"), coef, 1.0, f"aniso iterate {rx} {ry}")
 
 
 @pytest.mark.parametrize("MN", [(3, 3), (5, 5), (9, 9), (4, 3)])
