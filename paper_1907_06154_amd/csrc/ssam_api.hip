@@ -372,6 +372,40 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
         if (name) *name = inst->name;
         return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
     }
+    // No instance for these radii: embed the coefficient box, zero-padded, in the cheapest compiled
+    // shape with equal radii that covers it (a star in a wider star, anything in a box).
+    if (tu.force_generic <= 0 && tu.embed_waste != 0) {
+        const int budget = p.dtype == SSAM_F32
+                               ? tap_budget<float>((const float*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz)
+                               : tap_budget<double>((const double*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
+        const int need = p.rx > p.ry ? (p.rx > p.rz ? p.rx : p.rz) : (p.ry > p.rz ? p.ry : p.rz);
+        auto taps = [](const Instance3D& i) {
+            const long n = 2 * i.rx + 1;
+            return i.budget == 1 ? 6L * i.rx + 1 : i.budget == 2 ? n * n * n - 8L * i.rx * i.rx * i.rx : n * n * n;
+        };
+        const Instance3D* cube = nullptr;
+        for (const Instance3D& i : registry3d()) {
+            if (i.dtype != p.dtype || i.rx != i.ry || i.ry != i.rz || i.rx < need || i.budget < budget) continue;
+            if (i.variant != 0 || i.sweeps != 1) continue;
+            if (!cube || taps(i) < taps(*cube)) cube = &i;
+        }
+        if (cube) {
+            const int R = cube->rx, K = 2 * R + 1;
+            const int M = 2 * p.rx + 1, N = 2 * p.ry + 1, L = 2 * p.rz + 1;
+            const size_t es = elem(p.dtype);
+            std::vector<char> padded((size_t)K * K * K * es, 0);
+            const char* src = static_cast<const char*>(p.c);
+            for (int k = 0; k < L; ++k)
+                for (int n = 0; n < N; ++n)
+                    memcpy(&padded[((((size_t)(k + R - p.rz) * K) + (n + R - p.ry)) * K + (R - p.rx)) * es],
+                           src + ((size_t)k * N + n) * M * es, (size_t)M * es);
+            Problem3D q = p;
+            q.rx = q.ry = q.rz = R;
+            q.c = padded.data();
+            if (name) *name = std::string(cube->name) + "+embedded";
+            return cube->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        }
+    }
     if (name) *name = "generic_direct";
     if (geo) {
         *geo = Geometry();

@@ -83,6 +83,23 @@ def test_anisotropic_stencils_are_embedded(ssam, dtype):
         assert_parity(host(res), oracle.iterate(fld, coef, 3, "zero"), coef, 1.0, f"aniso iterate {rx} {ry}")
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_3d_shapes_without_instance_are_embedded(ssam, dtype):
+    """Unequal radii and radii between the compiled ones run zero-padded inside a compiled star or box."""
+    masks = [wl.mask_box(2, 1, 1), wl.mask_star(4, 2, 2), wl.mask_star(3, 3, 3), wl.mask_box(1, 1, 0), wl.mask_star(1, 0, 2)]
+    fld = wl.uniform_field((23, 30, 150), -1.0, 1.0, 531, dtype)
+    for k, mask in enumerate(masks):
+        coef = wl.seeded_coefficients(mask, 532 + k, dtype)
+        name = ssam.ssam_describe("stencil3d", fld.shape, coef, "zero").split()[0]
+        assert name.endswith("+embedded"), name
+        for boundary in ("clamp", "zero"):
+            print(f"embedded 3d {np.dtype(dtype).name} {coef.shape} {boundary} {name}", flush=True)
+            got = host(ssam.ssam_stencil3d(dev(fld), coef, boundary))
+            assert_parity(got, oracle.stencil(fld, coef, boundary), coef, 1.0, f"embedded3d {coef.shape} {boundary}")
+        res = ssam.ssam_stencil_iterate(dev(fld), torch.empty_like(dev(fld)), coef, 3, "zero")
+        assert_parity(host(res), oracle.iterate(fld, coef, 3, "zero"), coef, 1.0, f"embedded3d iterate {coef.shape}")
+
+
 @pytest.mark.parametrize("MN", [(3, 3), (5, 5), (9, 9), (4, 3)])
 def test_conv2d_f64_and_anchors(ssam, MN):
     M, N = MN
