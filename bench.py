@@ -37,27 +37,27 @@ ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}   # published vector peaks (fp32 f
 # kernels of the iterative 2D cases, by case and kernel instance; offline figures, not re-measured
 # by this script.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_conv3x3_f32": 554059143,
-    "c2_conv5x5_f32": 565128212,
-    "c2_conv9x9_f32": 571815793,
-    "c2_conv15x15_f32": 590394654,
-    "c2_conv20x20_f32": 600009449,
-    "c2_conv3x11_f32": 582322822,
-    "c2_conv11x3_f32": 551139449,
-    "c3_2d_box_r1_f64": 1102485294,
-    "c3_2d_box_r2_f64": 1083534618,
-    "c3_2d_star_r4_f64": 1129549854,
+    "c2_conv3x3_f32": 554222638,
+    "c2_conv5x5_f32": 564475129,
+    "c2_conv9x9_f32": 572090754,
+    "c2_conv15x15_f32": 589682368,
+    "c2_conv20x20_f32": 599764837,
+    "c2_conv3x11_f32": 583301232,
+    "c2_conv11x3_f32": 550761930,
+    "c3_2d_box_r1_f64": 1102608094,
+    "c3_2d_box_r2_f64": 1083636625,
+    "c3_2d_star_r4_f64": 1129602815,
     "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109809858,
     "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120402618,
     "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150222876,
-    "c4_3d_star_r1_f64": 2436739858,
-    "c4_3d_box_r1_f64": 2379723841,
-    "c4_3d_faces_edges_f64": 2382340545,
-    "c4_3d_star_r1_f64:double_r111_b1_v2p4f1nt2_fused2": 2319630654,
-    "c4_3d_box_r1_f64:double_r111_b3_v2p4f1nt2_fused2": 2511855644,
-    "c4_3d_faces_edges_f64:double_r111_b2_v2p4f0nt2_fused2": 2252243892,
-    "c5_3d_star_r4_f32": 1248362483,
-    "c5_3d_star_r4_f64": 2444633941,
+    "c4_3d_star_r1_f64": 2436359195,
+    "c4_3d_box_r1_f64": 2393105511,
+    "c4_3d_faces_edges_f64": 2340616190,
+    "c4_3d_star_r1_f64:double_r111_b1_v2p4f1nt2_fused2": 2306184564,
+    "c4_3d_box_r1_f64:double_r111_b3_v2p4f1nt2_fused2": 2530729982,
+    "c4_3d_faces_edges_f64:double_r111_b2_v2p4f0nt2_fused2": 2252338584,
+    "c5_3d_star_r4_f32": 1252768761,
+    "c5_3d_star_r4_f64": 2444375549,
 }
 
 
