@@ -190,13 +190,16 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     constexpr int M = Mask::kM, N = Mask::kN;
     constexpr int HL = (Mask::kLeft + V - 1) / V, HR = (Mask::kRight + V - 1) / V;
     Geometry g;
-    // arithmetic-bound filters use every lane they can; bandwidth-bound ones keep strips line-aligned
-    plan_strips(pr.W, V, HL, HR, tu.valid_lanes, &g, Mask::kNW < 64);
+    // Filters with about 30 taps or more are limited by instruction issue, or close to it: they use
+    // every lane they can and balance the tile count; bandwidth-bound ones keep strips line-aligned.
+    // (Measured on 8192^2 fp32: 6x6 645 -> 709, 7x7 523 -> 565 GStencil/s.)
+    constexpr bool kArith = Mask::kNW >= 30;
+    plan_strips(pr.W, V, HL, HR, tu.valid_lanes, &g, !kArith);
     g.P = P;
     int rows;
     if (tu.rows_per_wave > 0) {
         rows = tu.rows_per_wave;
-    } else if (Mask::kNW >= 64) {
+    } else if (kArith) {
         // arithmetic-heavy filters: every wave takes about the same time, so the tile count should
         // fill the machine's wave slots a whole number of times (a partly filled last round costs
         // a full one).  Measured on 8192^2, 20x20: 57 -> 73 GStencil/s.
