@@ -79,9 +79,13 @@ __device__ __forceinline__ T fetch(const GenericArgs<T>& a, int x, int y, int z)
 template <typename T>
 __global__ __launch_bounds__(256) void generic_kernel(const GenericArgs<T> a)
 {
-    const int x = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int y = blockIdx.y * 4 + (threadIdx.x >> 6);
-    const int z = blockIdx.z;
+    // blocks of 64 x 4 points, numbered x fastest in one grid dimension (the other two are too short
+    // for tall grids)
+    const unsigned nbx = (unsigned)(a.W + 63) / 64, nby = (unsigned)(a.H + 3) / 4;
+    const unsigned b = blockIdx.x;
+    const int x = (int)(b % nbx) * 64 + (threadIdx.x & 63);
+    const int y = (int)((b / nbx) % nby) * 4 + (threadIdx.x >> 6);
+    const int z = (int)(b / nbx / nby);
     if (x >= a.W || y >= a.H) return;
     T sum = T(0);
     if (a.star) {
@@ -167,9 +171,9 @@ hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, 
         for (int n = 0; n < N; ++n) a.w[K + n] = c[(az * N + n) * M + ax];
         for (int m = 0; m < M; ++m) a.w[K + N + m] = c[(az * N + ay) * M + m];
     }
-    if (ceil_div(H, 4) > 65535 || D > 65535) return hipErrorInvalidValue;
-    dim3 grid(ceil_div(W, 64), ceil_div(H, 4), D);
-    hipLaunchKernelGGL(generic_kernel<T>, grid, dim3(256), 0, stream, a);
+    const long long blocks = (long long)ceil_div(W, 64) * ceil_div(H, 4) * D;   // W*H*D < 2^31, so this fits
+    if (blocks > 2147483647LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -250,7 +250,9 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     g.rows_per_wave = P;
     const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
     g.tiles_y = ceil_div(LH, P);
-    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
+    // z-chunk per wave: short chunks (more waves, shorter tails) measured 3-5 % faster for radius 1
+    // on 512^3 in spite of the 2*RZ planes every chunk re-reads
+    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : (RZ == 1 ? 16 : 64);
     if (planes > LD) planes = LD;
     g.planes_per_wave = planes;
     g.tiles_z = ceil_div(LD, planes);

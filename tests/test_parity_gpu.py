@@ -408,3 +408,18 @@ def test_latency_probe_orders_the_primitives(ssam):
         ssam.ssam_probe_latency("fma_f32", 3, 1, 4096, scratch)
     with pytest.raises(ssam.SsamError):
         ssam.ssam_probe_latency("fma_f32", 1, 1, 4096, scratch[:1024])
+
+
+def test_direct_kernel_on_tall_and_deep_grids(ssam):
+    """The one-point-per-thread kernel numbers its blocks in one grid dimension, so extents beyond the
+    65535-block limit of the other two dimensions work (a filter too wide for any compiled box)."""
+    filt = wl.seeded_filter(23, 1, 601, np.float32)
+    img = wl.uniform_field((300000, 5), 0.0, 1.0, 602, np.float32)
+    assert ssam.ssam_describe("conv2d", img.shape, filt, "clamp").split()[0] == "generic_direct"
+    got = host(ssam.ssam_conv2d(dev(img), filt, "clamp"))
+    assert_parity(got, oracle.conv2d(img, filt, "clamp"), filt, 1.0, "tall grid, direct kernel")
+    coef = wl.seeded_coefficients(wl.mask_star(5, 5, 5), 603, np.float64)
+    fld = wl.uniform_field((70000, 3, 4), -1.0, 1.0, 604, np.float64)
+    assert ssam.ssam_describe("stencil3d", fld.shape, coef, "zero").split()[0] == "generic_direct"
+    got = host(ssam.ssam_stencil3d(dev(fld), coef, "zero"))
+    assert_parity(got, oracle.stencil(fld, coef, "zero"), coef, 1.0, "deep grid, direct kernel")
