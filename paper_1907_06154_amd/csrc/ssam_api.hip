@@ -25,6 +25,7 @@ std::vector<Instance3D>& registry3d()
 namespace {
 
 constexpr int kMaxFusedSweeps = 8;
+constexpr long long kFuseTwoMinPoints = 1LL << 22;
 std::atomic<int> g_rows_per_wave{-1}, g_valid_lanes{-1}, g_planes_per_wave{-1}, g_xcd_remap{-1},
     g_force_generic{-1}, g_variant{-1}, g_march_axis{-1}, g_fuse_sweeps{-1}, g_embed_waste{-1};
 
@@ -326,6 +327,10 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
     const int v = tu.variant > 0 ? tu.variant : 0;
     const bool flat = p.D == 1 && p.rz == 0;
     if (!flat && tu.march_axis == 1) return 0;
+    // Two sweeps per launch pay only on grids large enough to be bandwidth-bound (measured: from about
+    // 4M points); on smaller ones the fatter, fewer tiles lose more than the saved launch gains.  Three
+    // sweeps and more per launch were faster at every size tried (256^2 upwards).
+    const bool small = (long long)p.W * p.H * p.D < kFuseTwoMinPoints && tu.fuse_sweeps < 0;
     Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
     // the tightest tap shape any multi-sweep instance offers for this stencil: a deeper instance of a
     // wider shape (a box standing in for a star) is not taken over a shallower one of the exact shape
@@ -336,6 +341,7 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
         shape_budget = tight->budget;
     }
     for (int sweeps = max_sweeps; sweeps >= 2; --sweeps) {
+        if (sweeps == 2 && small) break;
         hipError_t e;
         if (flat) {
             const Instance2D* inst = p.dtype == SSAM_F32 ? pick2d<float>(q, true, v, sweeps) : pick2d<double>(q, true, v, sweeps);

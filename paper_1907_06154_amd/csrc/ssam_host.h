@@ -141,25 +141,42 @@ inline int wave_slots(const void* kernel)
 }
 
 // Rows per tile (a multiple of P, at least min_rows) such that strips * ceil(H / rows) tiles fill
-// `slots` wave slots k times as exactly as possible, for the smallest k that allows it.
+// `slots` wave slots k times as exactly as possible, for the smallest k that allows it.  A grid too
+// small to fill the slots even once gets the shortest tiles allowed (most waves).
 inline int balanced_rows(int H, int P, int strips, int slots, int min_rows)
 {
-    int best_rows = ceil_div(H, P) * P;
-    double best_eff = 0.0;
+    const int shortest = ceil_div(min_rows < P ? P : min_rows, P) * P;
+    auto fill = [&](int rows) {
+        const long tiles = (long)strips * ceil_div(H, rows);
+        const long rounds = (tiles + slots - 1) / slots;
+        return (double)tiles / ((double)rounds * slots);
+    };
+    int best_rows = shortest;
+    double best_eff = fill(shortest);
     for (int k = 1; k <= 4; ++k) {
         const int ytiles = slots * k / strips;
         if (ytiles < 1) continue;
         int rows = ceil_div(ceil_div(H, ytiles), P) * P;
-        if (rows < min_rows) rows = ceil_div(min_rows, P) * P;
-        const long tiles = (long)strips * ceil_div(H, rows);
-        const long rounds = (tiles + slots - 1) / slots;
-        const double eff = (double)tiles / ((double)rounds * slots);
-        if (eff > best_eff + 0.02) {
+        if (rows < shortest) rows = shortest;
+        const double eff = fill(rows);
+        // taller tiles amortise the rows re-read at tile tops: prefer them unless clearly less full
+        if (eff > best_eff + 0.02 || (rows > best_rows && eff > best_eff - 0.02)) {
             best_eff = eff;
             best_rows = rows;
         }
     }
     return best_rows;
+}
+
+// Planes per z-chunk of the 3D march: `preferred` where the grid is large enough to fill the wave
+// slots with it, otherwise fewer (never under `fewest`), so that a small grid still spreads over
+// the machine; every chunk re-reads its leading planes, which is why large grids keep `preferred`.
+inline int balanced_planes(int D, long tiles_xy, int slots, int preferred, int fewest)
+{
+    int planes = preferred < D ? preferred : D;
+    while (planes > fewest && tiles_xy * ceil_div(D, planes) < slots) planes = (planes + 1) / 2;
+    if (planes < fewest) planes = fewest < D ? fewest : D;
+    return planes;
 }
 
 inline void plan_blocks(Geometry* g, int remap_override)

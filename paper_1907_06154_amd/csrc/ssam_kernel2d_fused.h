@@ -191,11 +191,9 @@ hipError_t launch2d_fused(const Problem2D& pr, const Tuning& tu, Geometry* geo, 
     int rows;
     if (tu.rows_per_wave > 0) {
         rows = tu.rows_per_wave;
-    } else if (S >= 3) {
+    } else {
         static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_fused_kernel<T, V, P, Mask, S, NT>));
         rows = balanced_rows(pr.H, P, g.strips_x, slots, 8 * P);
-    } else {
-        rows = 64;
     }
     rows = ceil_div(rows, P) * P;
     if (rows > ceil_div(pr.H, P) * P) rows = ceil_div(pr.H, P) * P;

@@ -251,8 +251,12 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
     g.tiles_y = ceil_div(LH, P);
     // z-chunk per wave: short chunks (more waves, shorter tails) measured 3-5 % faster for radius 1
-    // on 512^3 in spite of the 2*RZ planes every chunk re-reads
-    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : (RZ == 1 ? 16 : 64);
+    // on 512^3 in spite of the 2*RZ planes every chunk re-reads; small grids get shorter ones still
+    int planes = tu.planes_per_wave;
+    if (planes <= 0) {
+        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam3d_kernel<T, V, P, RX, RY, RZ, BUDGET, NT, PREFETCH>));
+        planes = balanced_planes(LD, (long)g.strips_x * g.tiles_y, slots, RZ == 1 ? 16 : 64, 4 * RZ);
+    }
     if (planes > LD) planes = LD;
     g.planes_per_wave = planes;
     g.tiles_z = ceil_div(LD, planes);

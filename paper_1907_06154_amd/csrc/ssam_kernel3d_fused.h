@@ -174,7 +174,11 @@ hipError_t launch3d_fused(const Problem3D& pr, const Tuning& tu, Geometry* geo, 
     g.P = P;
     g.rows_per_wave = P;
     g.tiles_y = ceil_div(pr.H, P);
-    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
+    int planes = tu.planes_per_wave;
+    if (planes <= 0) {
+        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam3d_fused_kernel<T, V, P, RX, RY, RZ, BUDGET, NT, PREFETCH>));
+        planes = balanced_planes(pr.D, (long)g.strips_x * g.tiles_y, slots, 64, 8 * RZ);
+    }
     if (planes > pr.D) planes = pr.D;
     g.planes_per_wave = planes;
     g.tiles_z = ceil_div(pr.D, planes);

@@ -202,7 +202,20 @@ hipError_t launch3d_lds(const Problem3D& pr, const Tuning& tu, Geometry* geo, bo
     g.rows_per_wave = P;
     const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
     g.tiles_y = ceil_div(LH, NW * P);            // blocks of NW waves along the strip axis
-    int planes = tu.planes_per_wave > 0 ? tu.planes_per_wave : 64;
+    int planes = tu.planes_per_wave;
+    if (planes <= 0) {   // 64 planes per block where the grid fills the machine with that, fewer on small grids
+        int blocks_per_cu = 0, dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                &blocks_per_cu, reinterpret_cast<const void*>(&ssam3d_lds_kernel<T, V, P, NW, RX, RY, RZ, BUDGET, NT>),
+                NW * kWave, 0) != hipSuccess || blocks_per_cu <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+            blocks_per_cu = 2;
+        }
+        planes = balanced_planes(LD, (long)g.strips_x * g.tiles_y, cus * blocks_per_cu, 64, 4 * RZ);
+    }
     if (planes > LD) planes = LD;
     g.planes_per_wave = planes;
     g.tiles_z = ceil_div(LD, planes);
