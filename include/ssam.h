@@ -24,6 +24,10 @@
  *   - Results are deterministic run to run (no atomics); the order of additions differs
  *     from a sequential sum, so results agree with a reference to rounding, not bitwise.
  *   - Thread safety: calls may be made from several host threads on different streams.
+ *   - The compute entry points only enqueue kernels: no allocation, no memset, no synchronisation.
+ *     They may therefore be recorded by stream capture into a HIP graph and replayed (the host
+ *     arrays are read at capture time; make one ordinary call first so that one-time occupancy
+ *     queries are not part of the capture).
  */
 #ifndef SSAM_H_
 #define SSAM_H_
