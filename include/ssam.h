@@ -43,7 +43,8 @@ typedef enum {
     SSAM_ERR_NULL = 1,   /* a required pointer is NULL                                    */
     SSAM_ERR_DIM = 2,    /* W, H or D not positive, or the grid exceeds 2^31-1 elements   */
     SSAM_ERR_SHAPE = 3,  /* filter / radius not positive, anchor outside the filter, or
-                            larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0      */
+                            larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0; a
+                            dense coefficient box too large for any kernel (ssam_stencil3d) */
     SSAM_ERR_ENUM = 4,   /* unknown dtype or boundary value                               */
     SSAM_ERR_ALIAS = 5,  /* input and output buffers overlap                              */
     SSAM_ERR_HIP = 6     /* a HIP runtime call failed (no device, launch failure)         */
@@ -76,7 +77,11 @@ int ssam_stencil2d(const void *d_in, void *d_out, int W, int H,
 
 /* One sweep of a 3D stencil (paper Sec. 2.2 last paragraph, Sec. 4.9):
  *     out[z][y][x] = sum  h_coef[((dz+rz)*(2ry+1) + (dy+ry))*(2rx+1) + (dx+rx)] * IN(x+dx, y+dy, z+dz)
- * with the same zero-means-no-tap rule; Above = dz -1, Below = dz +1. */
+ * with the same zero-means-no-tap rule; Above = dz -1, Below = dz +1.
+ * Shapes with a compiled instance (or that fit zero-padded inside one: stars up to radius 4, boxes
+ * up to radius 2) run on the register-cache kernels; any other runs on a direct one-point-per-thread
+ * kernel whose coefficients travel in a 3584-byte argument block: a star of any radius fits, a
+ * dense box must have (2rx+1)(2ry+1)(2rz+1) elements within that size, else SSAM_ERR_SHAPE. */
 int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
                    const void *h_coef, int rx, int ry, int rz,
                    int boundary, int dtype, void *hip_stream);

@@ -1,0 +1,97 @@
+"""Seeded random sweep over the argument space of the four entry points: grid extents (including
+1 and values around tile seams), filter sizes and anchors, stencil radii per axis, star / box /
+sparse tap patterns, boundary rule, precision, step counts.  Every case is compared with the oracle
+element by element at the usual tolerance; the case list is fixed by the seed."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_06154_amd import workloads as wl
+from parity_util import assert_parity
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ssam():
+    import paper_1907_06154_amd as s
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    s.lib()
+    return s
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def extent(rng, big):
+    """An extent: often tiny, sometimes next to a tile seam (multiples of 56 lanes x 2 or 4 columns)."""
+    kind = rng.integers(0, 4)
+    if kind == 0:
+        return int(rng.integers(1, 9))
+    if kind == 1:
+        return int(rng.choice([112, 224, 448]) + rng.integers(-3, 4))
+    return int(rng.integers(9, big))
+
+
+def sparse_mask(rng, shape, centre):
+    m = rng.random(shape) < 0.5
+    m[centre] = True
+    return m
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_random_conv2d(ssam, block):
+    rng = np.random.default_rng(1000 + block)
+    for k in range(20):
+        dt = np.float32 if rng.integers(0, 3) else np.float64
+        H, W = extent(rng, 200), extent(rng, 700)
+        M, N = int(rng.integers(1, 22)), int(rng.integers(1, 22))
+        anchor = None if rng.integers(0, 2) else (int(rng.integers(0, M)), int(rng.integers(0, N)))
+        bnd = "clamp" if rng.integers(0, 2) else "zero"
+        filt = wl.seeded_filter(M, N, 2000 + 100 * block + k, dt)
+        img = wl.uniform_field((H, W), 0.0, 1.0, 3000 + 100 * block + k, dt)
+        print(f"random conv {np.dtype(dt).name} grid {H}x{W} filter {M}x{N} anchor {anchor} {bnd}", flush=True)
+        got = ssam.ssam_conv2d(dev(img), filt, bnd, anchor)
+        torch.cuda.synchronize()
+        assert_parity(got.cpu().numpy(), oracle.conv2d(img, filt, bnd, anchor), filt, 1.0,
+                      f"conv {H}x{W} {M}x{N} {anchor} {bnd}")
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_random_stencils(ssam, block):
+    rng = np.random.default_rng(5000 + block)
+    for k in range(16):
+        dt = np.float32 if rng.integers(0, 2) else np.float64
+        three_d = bool(rng.integers(0, 2))
+        bnd = "clamp" if rng.integers(0, 2) else "zero"
+        steps = int(rng.choice([1, 1, 2, 3, 4, 5, 7, 9]))
+        if three_d:
+            shape = (extent(rng, 40), extent(rng, 40), extent(rng, 300))
+            r = tuple(int(v) for v in rng.integers(0, 5, size=3))      # (rz, ry, rx)
+        else:
+            shape = (extent(rng, 200), extent(rng, 700))
+            r = (0,) + tuple(int(v) for v in rng.integers(0, 7, size=2))
+        box = tuple(2 * v + 1 for v in r)
+        pattern = rng.integers(0, 3)
+        if pattern == 0:
+            mask = wl.mask_star(r[2], r[1], r[0])
+        elif pattern == 1:
+            mask = wl.mask_box(r[2], r[1], r[0])
+        else:
+            mask = sparse_mask(rng, box, r)
+        # keep the oracle's time bounded, and stay inside what the ABI accepts: a dense coefficient box
+        # without a compiled shape to hold it must fit the direct kernel's 3584-byte argument block
+        if mask.sum() > 300 or mask.size * np.dtype(dt).itemsize > 3584:
+            mask = wl.mask_star(r[2], r[1], r[0])
+        coef = wl.seeded_coefficients(mask, 6000 + 100 * block + k, dt)
+        fld = wl.uniform_field(shape, -1.0, 1.0, 7000 + 100 * block + k, dt)
+        c = coef if three_d else coef[0]
+        print(f"random stencil {np.dtype(dt).name} grid {shape} radii {r} pattern {pattern} {bnd} steps {steps}", flush=True)
+        a = dev(fld)
+        res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), c, steps, bnd)
+        torch.cuda.synchronize()
+        assert_parity(res.cpu().numpy(), oracle.iterate(fld, c, steps, bnd), coef, 1.0,
+                      f"stencil {shape} {r} {pattern} {bnd} {steps}")
