@@ -44,20 +44,20 @@ MEASURED_TRAFFIC_BYTES = {
     "c2_conv20x20_f32": 599764837,
     "c2_conv3x11_f32": 583301232,
     "c2_conv11x3_f32": 550761930,
-    "c3_2d_box_r1_f64": 1102608094,
-    "c3_2d_box_r2_f64": 1083636625,
-    "c3_2d_star_r4_f64": 1129602815,
-    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109809858,
-    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120402618,
-    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150222876,
-    "c4_3d_star_r1_f64": 2436359195,
-    "c4_3d_box_r1_f64": 2393105511,
-    "c4_3d_faces_edges_f64": 2340616190,
-    "c4_3d_star_r1_f64:double_r111_b1_v2p4f1nt2_fused2": 2306184564,
-    "c4_3d_box_r1_f64:double_r111_b3_v2p4f1nt2_fused2": 2530729982,
-    "c4_3d_faces_edges_f64:double_r111_b2_v2p4f0nt2_fused2": 2252338584,
-    "c5_3d_star_r4_f32": 1252768761,
-    "c5_3d_star_r4_f64": 2444375549,
+    "c3_2d_box_r1_f64": 1102410735,
+    "c3_2d_box_r2_f64": 1113139258,
+    "c3_2d_star_r4_f64": 1129719290,
+    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109884661,
+    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120215410,
+    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150031958,
+    "c4_3d_star_r1_f64": 2439207291,
+    "c4_3d_box_r1_f64": 2347660545,
+    "c4_3d_faces_edges_f64": 2313081318,
+    "c4_3d_star_r1_f64:double_r111_b1_v2p4f1nt2_fused2": 2305148286,
+    "c4_3d_box_r1_f64:double_r111_b3_v2p4f1nt2_fused2": 2526118196,
+    "c4_3d_faces_edges_f64:double_r111_b2_v2p4f0nt2_fused2": 2252726714,
+    "c5_3d_star_r4_f32": 1252975790,
+    "c5_3d_star_r4_f64": 2446461759,
 }
 
 
