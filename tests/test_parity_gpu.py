@@ -465,3 +465,53 @@ def test_iterate_can_be_captured_in_a_hip_graph(ssam, shape, mask):
         # unrelated eager work between replays
         assert_parity(host(ssam.ssam_stencil_iterate(a0.clone(), torch.empty_like(a0), coef, 3, "zero")),
                       oracle.iterate(fld, coef, 3, "zero"), coef, 1.0, "eager between replays")
+
+
+def test_concurrent_host_threads_on_their_own_streams(ssam):
+    """Calls from several host threads, each on its own stream, give the results of serial calls
+    (the dispatcher keeps no per-call state; tuning globals are not touched here)."""
+    import threading
+    jobs = []
+    for k, (M, dt) in enumerate([(3, np.float32), (9, np.float32), (5, np.float64), (20, np.float32)]):
+        filt = wl.seeded_filter(M, M, 700 + k, dt)
+        img = wl.uniform_field((300, 1000), 0.0, 1.0, 710 + k, dt)
+        jobs.append((filt, img, oracle.conv2d(img, filt, "clamp")))
+    coef = wl.seeded_coefficients(wl.mask_star(1, 1, 1), 720, np.float64)
+    fld = wl.uniform_field((40, 50, 200), -1.0, 1.0, 721, np.float64)
+    want3 = oracle.iterate(fld, coef, 5, "zero")
+    results, errors = {}, []
+
+    def conv_worker(idx):
+        try:
+            filt, img, _ = jobs[idx]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                d = dev(img)
+                for _ in range(20):
+                    out = ssam.ssam_conv2d(d, filt, "clamp", stream=stream)
+                stream.synchronize()
+                results[idx] = out.cpu().numpy()
+        except Exception as e:   # surfaced in the main thread
+            errors.append(e)
+
+    def stencil_worker():
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                a = dev(fld)
+                for _ in range(10):
+                    res = ssam.ssam_stencil_iterate(a.clone(), torch.empty_like(a), coef, 5, "zero", stream=stream)
+                stream.synchronize()
+                results["s"] = res.cpu().numpy()
+        except Exception as e:
+            errors.append(e)
+
+    threads = [threading.Thread(target=conv_worker, args=(i,)) for i in range(len(jobs))] + [threading.Thread(target=stencil_worker)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for idx, (filt, _, want) in enumerate(jobs):
+        assert_parity(results[idx], want, filt, 1.0, f"thread {idx}")
+    assert_parity(results["s"], want3, coef, 1.0, "stencil thread")
