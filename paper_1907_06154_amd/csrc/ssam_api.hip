@@ -320,13 +320,12 @@ const Instance3D* pick3d(const Problem3D& p, int want_variant, int sweeps = 1)
 int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::string* name, int* rc)
 {
     const Tuning tu = current_tuning();
-    if (tu.fuse_sweeps == 0 || tu.fuse_sweeps == 1 || tu.force_generic > 0 || p.boundary != SSAM_BOUNDARY_ZERO)
-        return 0;
+    if (tu.fuse_sweeps == 0 || tu.fuse_sweeps == 1 || tu.force_generic > 0) return 0;
     if (tu.fuse_sweeps > 1 && tu.fuse_sweeps < max_sweeps) max_sweeps = tu.fuse_sweeps;
     if (max_sweeps > kMaxFusedSweeps) max_sweeps = kMaxFusedSweeps;
     const int v = tu.variant > 0 ? tu.variant : 0;
     const bool flat = p.D == 1 && p.rz == 0;
-    if (!flat && tu.march_axis == 1) return 0;
+    if (!flat && (tu.march_axis == 1 || p.boundary != SSAM_BOUNDARY_ZERO)) return 0;   // 3D: zero padding, z march
     // Two sweeps per launch pay only on grids large enough to be bandwidth-bound (measured: from about
     // 4M points); on smaller ones the fatter, fewer tiles lose more than the saved launch gains.  Three
     // sweeps and more per launch were faster at every size tried (256^2 upwards).

@@ -163,6 +163,19 @@ __device__ __forceinline__ double pick(double a, double b, unsigned m)
     return __builtin_bit_cast(double, x);
 }
 
+// Value of lane `l` (wave-uniform) broadcast to the whole wave.
+__device__ __forceinline__ float read_lane(float v, int l)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ double read_lane(double v, int l)
+{
+    Halves h = __builtin_bit_cast(Halves, v);
+    h.lo = __builtin_amdgcn_readlane(h.lo, l);
+    h.hi = __builtin_amdgcn_readlane(h.hi, l);
+    return __builtin_bit_cast(double, h);
+}
+
 // ---- tap masks ------------------------------------------------------------------------
 // Coefficients are run-time data; only the *shape* is compiled in, as in the paper's
 // one-instance-per-(M,N) template.  A mask describes one filter slice of width M (x) and

@@ -9,9 +9,13 @@
 // each end of the wave, so the wave stores 64 - 2*ceil(S*R/V) lanes, and each tile spends
 // ceil(2(S-1)R/P) extra groups at its top producing the intermediate rows its first outputs need.
 //
-// Zero padding only: an intermediate value at a position outside the grid must read as 0 for
-// the next sweep, which a mask does; under the clamp rule it would be the value of another
-// row or lane, so the dispatcher keeps clamp on the one-sweep kernel.
+// Boundary rule between sweeps (edge tiles only; interior tiles touch nothing outside the grid):
+// an intermediate value at a position outside the grid must read as 0 under zero padding, which a
+// mask does, and as the value of the nearest grid point under the clamp rule.  For columns that is
+// the value held by the lane that owns column 0 (or W-1), broadcast with v_readlane to the lanes
+// outside the grid.  For rows it is row 0 (or H-1) of the same sweep: rows above the grid are
+// produced before row 0 exists, so they are patched when they are consumed -- every window that
+// holds rows outside the grid and feeds a row inside it also holds row 0 (or H-1).
 #pragma once
 #include "ssam_kernel2d.h"
 
@@ -51,6 +55,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
     typedef Args2D<T, Mask::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
+    const bool clamp = a.boundary == kClamp;
 
     // The group with base y loads input rows y + S*R .. y + S*R + P-1; sweep k (0-based) turns
     // them into its rows y + (S-1-k)*R .. + P-1, and the last sweep's rows y .. y+P-1 are stored
@@ -61,13 +66,24 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
                           ys + (S - 2) * R >= 0 && y0 + (nchunks - 1) * P + S * R + P - 1 < H;
 
     auto march = [&](auto mode_tag) __attribute__((always_inline)) {
-        constexpr int MODE = decltype(mode_tag)::value;   // 0 interior, 1 general with vectors, 2 general by element
+        // 0 interior; edge tiles: 1 vectors / 2 by element with zero padding, 3 / 4 the same with the clamp rule
+        constexpr int MODE = decltype(mode_tag)::value;
         constexpr bool EDGE = MODE != 0;
-        constexpr bool VEC = MODE != 2;
+        constexpr bool VEC = MODE != 2 && MODE != 4;
+        constexpr bool CLAMP = MODE >= 3;
 
-        unsigned col_keep[V];   // all-ones where the lane's column lies inside the grid
+        unsigned col_keep[V], col_left[V], col_right[V];   // all-ones where the column lies inside / left of / right of the grid
 #pragma unroll
-        for (int i = 0; i < V; ++i) col_keep[i] = (xc + i >= 0 && xc + i < W) ? ~0u : 0u;
+        for (int i = 0; i < V; ++i) {
+            col_left[i] = xc + i < 0 ? ~0u : 0u;
+            col_right[i] = xc + i >= W ? ~0u : 0u;
+            col_keep[i] = ~(col_left[i] | col_right[i]);
+        }
+        // clamp rule: the lanes (wave-uniform) that own grid columns 0 and W-1, when they are in this wave
+        const int lane_first = __builtin_amdgcn_readfirstlane(min(max(-xw0, 0) / V, kWave - 1));
+        const int last_off = max(W - 1 - xw0, 0);
+        const int lane_last = __builtin_amdgcn_readfirstlane(min(last_off / V, kWave - 1));
+        const int elem_last = __builtin_amdgcn_readfirstlane(last_off % V);
 
         auto load_row = [&](int y, T (&dst)[V]) __attribute__((always_inline)) {
             if constexpr (!EDGE) {
@@ -77,11 +93,20 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
                 const T* rowp = in + (size_t)min(max(y, 0), H - 1) * W;
                 if constexpr (VEC) {
                     load_vec<T, V, (NT & kStreamLoads) != 0>(rowp + min(max(xl, 0), W - V), dst);
+                    if constexpr (CLAMP) {
+                        // columns outside the grid take the edge column, which is the first (last)
+                        // element of the vector such a lane loaded; rows were clamped in the address
+                        const T first = dst[0], last = dst[V - 1];
 #pragma unroll
-                    for (int i = 0; i < V; ++i) dst[i] = keep_if(dst[i], col_keep[0] & row_keep);
+                        for (int i = 0; i < V; ++i) dst[i] = pick(pick(dst[i], first, col_left[0]), last, col_right[0]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) dst[i] = keep_if(dst[i], col_keep[0] & row_keep);
+                    }
                 } else {
 #pragma unroll
-                    for (int i = 0; i < V; ++i) dst[i] = keep_if(rowp[min(max(xc + i, 0), W - 1)], col_keep[i] & row_keep);
+                    for (int i = 0; i < V; ++i)
+                        dst[i] = keep_if(rowp[min(max(xc + i, 0), W - 1)], CLAMP ? ~0u : (col_keep[i] & row_keep));
                 }
             }
         };
@@ -147,12 +172,60 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
                         else
                             systolic_rows<T, V, P, Mask, false>(RowPair<T, V, KEEP, P>{kept[k], mid[k > 0 ? k - 1 : 0]}, wts, mid[k], mid[k]);
                         if constexpr (EDGE) {
+                            if constexpr (!CLAMP) {
 #pragma unroll
-                            for (int p = 0; p < P; ++p) {
-                                const int yr = y + (S - 1 - k) * R + p;
-                                const unsigned row_keep = (yr >= 0 && yr < H) ? ~0u : 0u;
+                                for (int p = 0; p < P; ++p) {
+                                    const int yr = y + (S - 1 - k) * R + p;
+                                    const unsigned row_keep = (yr >= 0 && yr < H) ? ~0u : 0u;
 #pragma unroll
-                                for (int i = 0; i < V; ++i) mid[k][p][i] = keep_if(mid[k][p][i], col_keep[VEC ? 0 : i] & row_keep);
+                                    for (int i = 0; i < V; ++i)
+                                        mid[k][p][i] = keep_if(mid[k][p][i], col_keep[VEC ? 0 : i] & row_keep);
+                                }
+                            } else {
+                                // columns outside the grid take this sweep's value at column 0 / W-1
+#pragma unroll
+                                for (int p = 0; p < P; ++p) {
+                                    const T bl = read_lane(mid[k][p][0], lane_first);
+                                    T pickd = mid[k][p][0];
+#pragma unroll
+                                    for (int i = 1; i < V; ++i) pickd = pick(pickd, mid[k][p][i], elem_last == i ? ~0u : 0u);
+                                    const T br = read_lane(pickd, lane_last);
+#pragma unroll
+                                    for (int i = 0; i < V; ++i)
+                                        mid[k][p][i] = pick(pick(mid[k][p][i], bl, col_left[VEC ? 0 : i]), br, col_right[VEC ? 0 : i]);
+                                }
+                                // rows outside the grid, in the window the next sweep is about to read
+                                // (kept[k+1] then mid[k]), take row 0 / H-1 of this sweep
+                                const int wb = y + (S - 1 - k) * R - KEEP;   // grid row of the window's first row
+                                if (wb < 0 || wb + KEEP + P - 1 >= H) {
+                                    T r0[V], rl[V];
+#pragma unroll
+                                    for (int i = 0; i < V; ++i) r0[i] = rl[i] = T(0);
+#pragma unroll
+                                    for (int q = 0; q < KEEP + P; ++q) {
+                                        const unsigned m0 = wb + q == 0 ? ~0u : 0u, ml = wb + q == H - 1 ? ~0u : 0u;
+#pragma unroll
+                                        for (int i = 0; i < V; ++i) {
+                                            const T v = q < KEEP ? kept[k + 1][q < KEEP ? q : 0][i] : mid[k][q >= KEEP ? q - KEEP : 0][i];
+                                            r0[i] = pick(r0[i], v, m0);
+                                            rl[i] = pick(rl[i], v, ml);
+                                        }
+                                    }
+#pragma unroll
+                                    for (int q = 0; q < KEEP + P; ++q) {
+                                        const unsigned lo = wb + q < 0 ? ~0u : 0u, hi = wb + q >= H ? ~0u : 0u;
+#pragma unroll
+                                        for (int i = 0; i < V; ++i) {
+                                            if (q < KEEP) {
+                                                T& v = kept[k + 1][q < KEEP ? q : 0][i];
+                                                v = pick(pick(v, r0[i], lo), rl[i], hi);
+                                            } else {
+                                                T& v = mid[k][q >= KEEP ? q - KEEP : 0][i];
+                                                v = pick(pick(v, r0[i], lo), rl[i], hi);
+                                            }
+                                        }
+                                    }
+                                }
                             }
                         }
                     });
@@ -171,8 +244,10 @@ __global__ __launch_bounds__(kBlock) void ssam2d_fused_kernel(const Args2D<T, Ma
     };
 
     if (interior) march(std::integral_constant<int, 0>{});
-    else if (vec_ok) march(std::integral_constant<int, 1>{});
-    else march(std::integral_constant<int, 2>{});
+    else if (!clamp && vec_ok) march(std::integral_constant<int, 1>{});
+    else if (!clamp) march(std::integral_constant<int, 2>{});
+    else if (vec_ok) march(std::integral_constant<int, 3>{});
+    else march(std::integral_constant<int, 4>{});
 }
 
 template <typename T, int V, int P, class Mask, int S, int NT>
@@ -181,7 +256,6 @@ hipError_t launch2d_fused(const Problem2D& pr, const Tuning& tu, Geometry* geo, 
     constexpr int M = Mask::kM, N = Mask::kN;
     constexpr int HL = (S * Mask::kLeft + V - 1) / V;
     static_assert(64 - 2 * HL >= 8, "stencil too wide for this many sweeps in one wave");
-    if (pr.boundary != SSAM_BOUNDARY_ZERO) return hipErrorInvalidValue;
     Geometry g;
     plan_strips(pr.W, V, HL, HL, tu.valid_lanes, &g, true);
     g.P = P;

@@ -249,26 +249,27 @@ def test_fused_sweeps_match_oracle(ssam, dtype, kind, r):
     mask = wl.mask_box(r, r) if kind == "box" else wl.mask_star(r, r)
     coef = wl.seeded_coefficients(mask, 820 + r, dtype)[0]
     assert "_fused" in ssam.ssam_describe("iterate2d", (4096, 4096), coef, "zero")
-    assert "_fused" not in ssam.ssam_describe("iterate2d", (4096, 4096), coef, "clamp")
+    assert "_fused" in ssam.ssam_describe("iterate2d", (4096, 4096), coef, "clamp")
     for shape in FUSED_SHAPES:
         fld = wl.uniform_field(shape, -1.0, 1.0, 830 + shape[0], dtype)
-        for steps in (2, 3, 4, 5, 6, 7, 9):
-            want = oracle.iterate(fld, coef, steps, "zero")
-            for fuse in (-1, 0, 2, 3):
-                print(f"fused {np.dtype(dtype).name} {kind} r{r} {shape} steps {steps} fuse {fuse}", flush=True)
-                ssam.ssam_set_tuning("fuse_sweeps", fuse)
-                try:
-                    launches = planned_launches(ssam, shape, coef, steps, "zero")
-                    a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
-                    res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
-                finally:
-                    ssam.ssam_set_tuning("fuse_sweeps", -1)
-                # (grids this small run a remaining pair of sweeps as two launches unless a cap asks for pairs)
-                assert launches == steps if fuse == 0 else launches <= steps
-                if fuse != 0 and (fuse in (2, 3) or (steps >= 3 and r <= 4)):
-                    assert launches < steps
-                assert res.data_ptr() == (a if launches % 2 == 0 else b).data_ptr()
-                assert_parity(host(res), want, coef, 1.0, f"fused {kind} r{r} {shape} steps {steps} fuse {fuse}")
+        for boundary in ("zero", "clamp"):
+            for steps in (2, 3, 4, 5, 6, 7, 9):
+                want = oracle.iterate(fld, coef, steps, boundary)
+                for fuse in (-1, 0, 2, 3):
+                    print(f"fused {np.dtype(dtype).name} {kind} r{r} {shape} {boundary} steps {steps} fuse {fuse}", flush=True)
+                    ssam.ssam_set_tuning("fuse_sweeps", fuse)
+                    try:
+                        launches = planned_launches(ssam, shape, coef, steps, boundary)
+                        a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+                        res = ssam.ssam_stencil_iterate(a, b, coef, steps, boundary)
+                    finally:
+                        ssam.ssam_set_tuning("fuse_sweeps", -1)
+                    # (grids this small run a remaining pair of sweeps as two launches unless a cap asks for pairs)
+                    assert launches == steps if fuse == 0 else launches <= steps
+                    if fuse != 0 and (fuse in (2, 3) or (steps >= 3 and r <= 4)):
+                        assert launches < steps
+                    assert res.data_ptr() == (a if launches % 2 == 0 else b).data_ptr()
+                    assert_parity(host(res), want, coef, 1.0, f"fused {kind} r{r} {shape} {boundary} steps {steps} fuse {fuse}")
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
@@ -288,9 +289,17 @@ def test_fused_sweeps_tile_overrides_and_clamp(ssam, dtype):
         finally:
             for k in tuning:
                 ssam.ssam_set_tuning(k, -1)
-    a = dev(fld)
-    res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), coef, 4, "clamp")
-    assert_parity(host(res), oracle.iterate(fld, coef, 4, "clamp"), coef, 1.0, "clamp stays on single sweeps")
+    want = oracle.iterate(fld, coef, 4, "clamp")
+    for tuning in ({}, {"rows_per_wave": 8}, {"rows_per_wave": 40, "valid_lanes": 17}, {"fuse_sweeps": 2, "variant": 1}):
+        for k, v in tuning.items():
+            ssam.ssam_set_tuning(k, v)
+        try:
+            a = dev(fld)
+            res = ssam.ssam_stencil_iterate(a, torch.empty_like(a), coef, 4, "clamp")
+            assert_parity(host(res), want, coef, 1.0, f"fused clamp {tuning}")
+        finally:
+            for k in tuning:
+                ssam.ssam_set_tuning(k, -1)
 
 
 FUSED_SHAPES_3D = [(1, 1, 1), (3, 5, 7), (9, 33, 130), (20, 13, 140), (70, 10, 224), (17, 40, 300)]
