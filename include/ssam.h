@@ -90,8 +90,10 @@ int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
  * launch reading one and writing the other; every grid point is updated each sweep, the
  * boundary rule supplying reads outside the grid.  D == 1 with rz == 0 is the 2D case.
  * A launch performs one sweep, or -- where the shape has a compiled multi-sweep instance (2D,
- * either boundary rule: up to 8 sweeps; 3D radius 1 and 2, zero padding: two) -- several sweeps with the intermediate fields held in registers (temporal blocking,
- * which Sec. 6.4 says the model permits); the result is the same field to rounding either way.
+ * either boundary rule: up to 8 sweeps; 3D radius 1 and 2: two, under the clamp rule the
+ * 7-point star only) -- several sweeps with the intermediate fields held in registers (temporal
+ * blocking, which Sec. 6.4 says the model permits); the result is the same field to rounding
+ * either way.
  * *d_result (host location, may be NULL) receives the buffer that holds the field after
  * `steps` sweeps: d_a when the number of LAUNCHES is even (steps == 0 does nothing), d_b when
  * it is odd -- read it rather than infer it from `steps`.  Both buffers are overwritten when

@@ -325,7 +325,7 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
     if (max_sweeps > kMaxFusedSweeps) max_sweeps = kMaxFusedSweeps;
     const int v = tu.variant > 0 ? tu.variant : 0;
     const bool flat = p.D == 1 && p.rz == 0;
-    if (!flat && (tu.march_axis == 1 || p.boundary != SSAM_BOUNDARY_ZERO)) return 0;   // 3D: zero padding, z march
+    if (!flat && tu.march_axis == 1) return 0;   // 3D: z march only
     // Two sweeps per launch pay only on grids large enough to be bandwidth-bound (measured: from about
     // 4M points); on smaller ones the fatter, fewer tiles lose more than the saved launch gains.  Three
     // sweeps and more per launch were faster at every size tried (256^2 upwards).
@@ -352,7 +352,7 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
         } else {
             const Instance3D* inst = p.dtype == SSAM_F32 ? pick3d<float>(p, v, sweeps) : pick3d<double>(p, v, sweeps);
             if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p, 0, sweeps) : pick3d<double>(p, 0, sweeps);
-            if (!inst) continue;
+            if (!inst || (p.boundary == SSAM_BOUNDARY_CLAMP && !inst->fuses_clamp)) continue;
             if (name) *name = inst->name;
             e = inst->launch(p, tu, geo, dry);
         }

@@ -78,7 +78,8 @@ struct Instance3D {
     int dtype, rx, ry, rz, budget;  // budget = max number of non-zero offset components (1 star, 2, 3 box)
     int variant;
     Launch3DFn launch;
-    int sweeps = 1;                 // Jacobi sweeps one launch performs (2: the fused kernel, zero padding, z march only)
+    int sweeps = 1;                 // Jacobi sweeps one launch performs (2: the fused kernel, z march only)
+    bool fuses_clamp = false;       // the fused kernel also exists for the clamp rule (where it measured faster)
 };
 
 std::vector<Instance2D>& registry2d();

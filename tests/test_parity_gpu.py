@@ -318,30 +318,33 @@ def test_fused_sweeps_3d_match_oracle(ssam, dtype, kind):
     # and the fp64 radius-2 star
     has_fused = not (kind == "box" and dtype == np.float32) and not (kind == "star_r2" and dtype == np.float64)
     assert ssam.ssam_describe("iterate3d", (512, 512, 512), coef, "zero").split()[0].endswith("_fused2") == has_fused
-    assert "_fused" not in ssam.ssam_describe("iterate3d", (512, 512, 512), coef, "clamp")
+    # ... and under the clamp rule only the 7-point star has one
+    assert ssam.ssam_describe("iterate3d", (512, 512, 512), coef, "clamp").split()[0].endswith("_fused2") == (kind == "star")
     assert "_fused" not in ssam.ssam_describe("iterate3d", (64, 64, 64), coef, "zero")   # too small to pay
     for shape in FUSED_SHAPES_3D:
         fld = wl.uniform_field(shape, -1.0, 1.0, 860 + shape[0], dtype)
-        for steps in (2, 3, 4, 5):
-            want = oracle.iterate(fld, coef, steps, "zero")
-            # fuse_sweeps = 2 asks for pairs whatever the grid size; the default leaves grids this small unfused
-            for tuning in ({"fuse_sweeps": 2}, {}, {"fuse_sweeps": 0}, {"fuse_sweeps": 2, "variant": 1},
-                           {"fuse_sweeps": 2, "planes_per_wave": 3},
-                           {"fuse_sweeps": 2, "valid_lanes": 9, "planes_per_wave": 5}, {"fuse_sweeps": 2, "march_axis": 1}):
-                print(f"fused3d {np.dtype(dtype).name} {kind} {shape} steps {steps} {tuning}", flush=True)
-                for k, v in tuning.items():
-                    ssam.ssam_set_tuning(k, v)
-                try:
-                    fused = "_fused2" in ssam.ssam_describe("iterate3d", shape, coef, "zero")
-                    a, b = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
-                    res = ssam.ssam_stencil_iterate(a, b, coef, steps, "zero")
-                finally:
-                    for k in tuning:
-                        ssam.ssam_set_tuning(k, -1)
-                assert fused == (has_fused and tuning.get("fuse_sweeps") == 2 and tuning.get("march_axis") != 1)
-                launches = steps // 2 + steps % 2 if fused else steps
-                assert res.data_ptr() == (a if launches % 2 == 0 else b).data_ptr()
-                assert_parity(host(res), want, coef, 1.0, f"fused3d {kind} {shape} steps {steps} {tuning}")
+        for boundary in ("zero", "clamp"):
+            for steps in (2, 3, 4, 5):
+                want = oracle.iterate(fld, coef, steps, boundary)
+                # fuse_sweeps = 2 asks for pairs whatever the grid size; the default leaves grids this small unfused
+                for tuning in ({"fuse_sweeps": 2}, {}, {"fuse_sweeps": 0}, {"fuse_sweeps": 2, "variant": 1},
+                               {"fuse_sweeps": 2, "planes_per_wave": 3}, {"fuse_sweeps": 2, "planes_per_wave": 1},
+                               {"fuse_sweeps": 2, "valid_lanes": 9, "planes_per_wave": 5}, {"fuse_sweeps": 2, "march_axis": 1}):
+                    print(f"fused3d {np.dtype(dtype).name} {kind} {shape} {boundary} steps {steps} {tuning}", flush=True)
+                    for k, v in tuning.items():
+                        ssam.ssam_set_tuning(k, v)
+                    try:
+                        fused = "_fused2" in ssam.ssam_describe("iterate3d", shape, coef, boundary)
+                        a_, b_ = dev(fld), torch.full(shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+                        res = ssam.ssam_stencil_iterate(a_, b_, coef, steps, boundary)
+                    finally:
+                        for k in tuning:
+                            ssam.ssam_set_tuning(k, -1)
+                    assert fused == (has_fused and (boundary == "zero" or kind == "star") and
+                                     tuning.get("fuse_sweeps") == 2 and tuning.get("march_axis") != 1)
+                    launches = steps // 2 + steps % 2 if fused else steps
+                    assert res.data_ptr() == (a_ if launches % 2 == 0 else b_).data_ptr()
+                    assert_parity(host(res), want, coef, 1.0, f"fused3d {kind} {shape} {boundary} steps {steps} {tuning}")
 
 
 def test_results_are_bitwise_reproducible(ssam):
