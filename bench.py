@@ -37,19 +37,19 @@ ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}   # published vector peaks (fp32 f
 # kernels of the iterative 2D cases, by case and kernel instance; offline figures, not re-measured
 # by this script.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_conv3x3_f32": 554222638,
-    "c2_conv5x5_f32": 564475129,
-    "c2_conv9x9_f32": 572090754,
-    "c2_conv15x15_f32": 589682368,
-    "c2_conv20x20_f32": 599764837,
-    "c2_conv3x11_f32": 583301232,
-    "c2_conv11x3_f32": 550761930,
-    "c3_2d_box_r1_f64": 1102410735,
-    "c3_2d_box_r2_f64": 1113139258,
-    "c3_2d_star_r4_f64": 1129719290,
-    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109884661,
-    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120215410,
-    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150031958,
+    "c2_conv3x3_f32": 537656079,
+    "c2_conv5x5_f32": 538267998,
+    "c2_conv9x9_f32": 571909623,
+    "c2_conv15x15_f32": 588413804,
+    "c2_conv20x20_f32": 599690591,
+    "c2_conv3x11_f32": 575995544,
+    "c2_conv11x3_f32": 553120003,
+    "c3_2d_box_r1_f64": 1075826419,
+    "c3_2d_box_r2_f64": 1076305303,
+    "c3_2d_star_r4_f64": 1078286643,
+    "c3_2d_box_r1_f64:double_R1_b2_v2p4nt2_fused8": 1109794685,
+    "c3_2d_box_r2_f64:double_R2_b2_v2p4nt2_fused4": 1120376530,
+    "c3_2d_star_r4_f64:double_R4_b1_v2p4nt2_fused3": 1150265600,
     "c4_3d_star_r1_f64": 2439207291,
     "c4_3d_box_r1_f64": 2347660545,
     "c4_3d_faces_edges_f64": 2313081318,

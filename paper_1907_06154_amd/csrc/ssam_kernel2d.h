@@ -206,7 +206,11 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
         static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_kernel<T, V, P, Mask, PREFETCH, NT>));
         rows = balanced_rows(pr.H, P, g.strips_x, slots, 3 * (N - 1));
     } else {
-        rows = N <= 5 ? 32 : 64;   // bandwidth-bound: short tiles measured best
+        // bandwidth-bound: the shortest tiles measured best -- one or two groups per wave, about twice the
+        // N-1 rows a tile re-reads at its top (8192^2: 3x3 fp32 839 -> 918 GStencil/s from 32 to 8 rows,
+        // 5x5 760 -> 858, fp64 17-point star 343 -> 370 from 64 to 16); many short waves sweep the grid
+        // in step and finish together, which matters more than the re-read rows, which hit in L2
+        rows = 2 * (N - 1) > P ? 2 * (N - 1) : P;
     }
     rows = ceil_div(rows, P) * P;
     if (rows > ceil_div(pr.H, P) * P) rows = ceil_div(pr.H, P) * P;
