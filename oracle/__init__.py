@@ -119,3 +119,18 @@ def iterate(field: np.ndarray, coef: np.ndarray, steps: int, boundary: str = "ze
     if which < 0:
         raise ValueError("oracle_iterate rejected its arguments")
     return a if which == 0 else b
+
+
+def scan(values: np.ndarray) -> np.ndarray:
+    """Inclusive prefix sums of a 1D array (running total in the accumulation type, each prefix
+    rounded to the array's type)."""
+    a = np.ascontiguousarray(values)
+    if a.ndim != 1:
+        raise ValueError("scan takes a 1D array")
+    b = np.empty_like(a)
+    fn = getattr(_load(), "oracle_scan_" + _suffix(a.dtype))
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_long]
+    if fn(_ptr(a) if a.size else None, _ptr(b) if a.size else None, a.size) != 0:
+        raise ValueError("oracle_scan rejected its arguments")
+    return b

@@ -2,6 +2,7 @@
 itself (exact rational arithmetic written a different way, closed forms, hand-worked values
 from the equations of Sec. 2.1 / 2.2, scipy.ndimage and torch routines, identities).
 None of these tests needs a GPU."""
+import math
 from fractions import Fraction
 
 import numpy as np
@@ -400,3 +401,45 @@ def test_windowed_oracle_equals_full_grid_oracle(kind):
     for lo, hi in wins:
         sl = tuple(slice(l, h) for l, h in zip(lo, hi))
         assert np.array_equal(oracle_window(case, lo, hi), full[sl])
+
+
+# ---- scan (Sec. 3.6) ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_scan_matches_exact_rational_prefix_sums(dtype):
+    """Prefix sums of short arrays against exact rational arithmetic, rounded once to the type."""
+    from fractions import Fraction
+    rng = np.random.default_rng(7)
+    for n in (1, 2, 3, 17, 50):
+        a = rng.uniform(-1.0, 1.0, n).astype(dtype)
+        got = oracle.scan(a)
+        run = Fraction(0)
+        for i in range(n):
+            run += Fraction(float(a[i]))
+            want = dtype(float(run)) if dtype == np.float64 else np.float32(float(run))
+            assert abs(float(got[i]) - float(want)) <= (0.0 if dtype == np.float32 else 2.3e-16 * max(1.0, abs(float(want)))), (n, i)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_scan_closed_forms_and_edges(dtype):
+    assert oracle.scan(np.zeros(0, dtype=dtype)).shape == (0,)
+    assert np.array_equal(oracle.scan(np.array([2.5], dtype=dtype)), np.array([2.5], dtype=dtype))
+    n = 4000
+    assert np.array_equal(oracle.scan(np.ones(n, dtype=dtype)), np.arange(1, n + 1).astype(dtype))
+    ramp = np.arange(1, n + 1).astype(dtype)                      # 1 + 2 + ... + i = i (i + 1) / 2, exact here
+    assert np.array_equal(oracle.scan(ramp), (np.arange(1, n + 1) * np.arange(2, n + 2) // 2).astype(dtype))
+    alt = np.where(np.arange(n) % 2 == 0, 1.0, -1.0).astype(dtype)
+    assert np.array_equal(oracle.scan(alt), (np.arange(n) % 2 == 0).astype(dtype))
+    # a sign error or an exclusive scan would break this one: last prefix is the total, first is a_0
+    a = wl.uniform_field((1000,), -1.0, 1.0, 77, dtype)
+    got = oracle.scan(a)
+    assert got[0] == a[0]
+    assert abs(float(got[-1]) - math.fsum(float(v) for v in a)) <= (1e-5 if dtype == np.float32 else 1e-13)
+    # differences of consecutive prefixes give the input back (to rounding)
+    back = np.diff(np.concatenate([[0.0], got.astype(np.float64)]))
+    assert np.max(np.abs(back - a.astype(np.float64))) <= (1e-5 if dtype == np.float32 else 1e-13)
+
+
+def test_scan_fp32_is_sequential_double_accumulation():
+    a = wl.uniform_field((100000,), 0.0, 1.0, 78, np.float32)
+    assert np.array_equal(oracle.scan(a), np.cumsum(a.astype(np.float64)).astype(np.float32))
