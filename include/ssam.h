@@ -113,7 +113,9 @@ const char *ssam_status_string(int status);
  * 1 = march along y), "fuse_sweeps" (ssam_stencil_iterate: 0 or 1 = always one sweep per launch, n >= 2 = at most n),
  * "embed_waste" (a 2D filter shape without a compiled instance runs inside the smallest compiled
  * square box that holds it, zero-padded; a value n >= 0 allows that only while the box has at most
- * n times its taps, 0 = never: such shapes then use the direct one-point-per-thread kernel).
+ * n times its taps, 0 = never: such shapes then use the direct one-point-per-thread kernel),
+ * "scan_segments" (ssam_scan: upper limit of segments, 1 .. 32768; ssam_scan_workspace_bytes
+ * follows it), "scan_order" (0 = the last launch of ssam_scan takes the segments first to last).
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 
@@ -129,6 +131,28 @@ int ssam_set_tuning(const char *name, int value);
  * blocking (Sec. 4.5, Sec. 4.7) re-derived for 64 lanes of V columns each. */
 int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
                   int boundary, int dtype, char *buf, int buflen);
+
+/* Inclusive scan of a 1D array, b_i = a_0 + a_1 + ... + a_i for 0 <= i < n (Sec. 3.6: partial
+ * sums shifted between the lanes of a wave, every lane holding several consecutive elements in
+ * registers).  d_in, d_out: device, n contiguous elements of dtype, aligned to the element
+ * size (16-byte alignment of both selects the vector-access kernels); d_out may be the same
+ * pointer as d_in (in place), any other overlap gives SSAM_ERR_ALIAS.  d_work: device
+ * workspace of at least ssam_scan_workspace_bytes(n, dtype) bytes, 8-byte aligned, not
+ * overlapping the arrays, owned by the caller and free for reuse once the call's work on
+ * hip_stream has finished; it may be NULL when that size is 0 (short arrays).  The array is
+ * cut into contiguous segments, one per wave; three launches are enqueued on hip_stream (segment
+ * sums, their exclusive prefixes, the scan of every segment) and the call returns without
+ * waiting and without allocating.  Totals that cross a 64-lane step are carried in fp64 for both
+ * element types, so the fp32 result is within a few fp32 roundings of the exact prefix, relative
+ * to the sum of magnitudes.  n == 0 is a no-op.  Errors: SSAM_ERR_ENUM (dtype), SSAM_ERR_DIM
+ * (n < 0, misaligned pointer, workspace too small), SSAM_ERR_NULL, SSAM_ERR_ALIAS, SSAM_ERR_HIP. */
+int ssam_scan(const void *d_in, void *d_out, long long n, int dtype,
+              void *d_work, size_t work_bytes, void *hip_stream);
+
+/* Host only: bytes of workspace ssam_scan needs for n elements of dtype under the current
+ * tuning (8 bytes per segment, at most 256 KiB; 0 when one segment suffices or the arguments
+ * are invalid). */
+size_t ssam_scan_workspace_bytes(long long n, int dtype);
 
 /* Measurement aid: copies nbytes (a multiple of 16; both pointers 16-byte aligned, not
  * overlapping) from d_in to d_out with a plain 16-bytes-per-lane kernel on hip_stream.  It is

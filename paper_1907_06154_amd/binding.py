@@ -20,7 +20,8 @@ SSAM_F32, SSAM_F64 = 0, 1
 SSAM_BOUNDARY_ZERO, SSAM_BOUNDARY_CLAMP = 0, 1
 BOUNDARY = {"zero": SSAM_BOUNDARY_ZERO, "clamp": SSAM_BOUNDARY_CLAMP}
 EXPORTS = ["ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
-           "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy", "ssam_probe_latency"]
+           "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy", "ssam_probe_latency",
+           "ssam_scan", "ssam_scan_workspace_bytes"]
 
 
 class SsamError(RuntimeError):
@@ -51,9 +52,12 @@ def lib() -> ctypes.CDLL:
         L.ssam_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.ssam_probe_latency.argtypes = [ci, ci, ci, ci, vp, ctypes.c_size_t, vp, vp]
         L.ssam_probe_latency.restype = ci
+        L.ssam_scan.argtypes = [vp, vp, ctypes.c_longlong, ci, vp, ctypes.c_size_t, vp]
+        L.ssam_scan_workspace_bytes.argtypes = [ctypes.c_longlong, ci]
         for name in EXPORTS:
-            if name not in ("ssam_status_string",):
+            if name not in ("ssam_status_string", "ssam_scan_workspace_bytes"):
                 getattr(L, name).restype = ci
+        L.ssam_scan_workspace_bytes.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -220,6 +224,36 @@ def ssam_describe(kind: str, shape, coef, boundary: str = "zero", remaining: int
         raise ValueError(kind)
     _check(st, "ssam_describe")
     return buf.value.decode()
+
+
+def ssam_scan_workspace_bytes(n: int, dtype) -> int:
+    """Workspace size ssam_scan needs for n elements (dtype: a torch or numpy float32/float64)."""
+    code = SSAM_F32 if "32" in str(dtype) else SSAM_F64 if "64" in str(dtype) else -1
+    return int(lib().ssam_scan_workspace_bytes(int(n), code))
+
+
+def ssam_scan(d_in, d_out=None, d_work=None, stream=None):
+    """Inclusive prefix sums of a 1D device tensor.  d_out: result tensor (default: a new one;
+    passing d_in itself scans in place).  d_work: a byte workspace tensor of at least
+    ssam_scan_workspace_bytes(n, dtype) bytes (default: a new one)."""
+    import torch
+    _device_tensor(d_in, "d_in")
+    if d_in.dim() != 1:
+        raise ValueError("ssam_scan takes a 1D tensor")
+    code = _dtype_code(d_in)
+    if d_out is None:
+        d_out = torch.empty_like(d_in)
+    _device_tensor(d_out, "d_out")
+    if d_out.shape != d_in.shape or d_out.dtype != d_in.dtype:
+        raise ValueError("d_out must match d_in in shape and dtype")
+    n = d_in.numel()
+    need = int(lib().ssam_scan_workspace_bytes(n, code))
+    if d_work is None and need:
+        d_work = torch.empty(need, dtype=torch.uint8, device=d_in.device)
+    wp, wb = (d_work.data_ptr(), d_work.numel() * d_work.element_size()) if d_work is not None else (None, 0)
+    _check(lib().ssam_scan(d_in.data_ptr() if n else None, d_out.data_ptr() if n else None, n, code,
+                           wp, wb, _stream_ptr(stream)), "ssam_scan")
+    return d_out
 
 
 def ssam_probe_copy(d_in, d_out, stream=None):

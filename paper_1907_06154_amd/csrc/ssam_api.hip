@@ -567,6 +567,8 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "march_axis")) g_march_axis = value;
     else if (!strcmp(name, "fuse_sweeps")) g_fuse_sweeps = value;
     else if (!strcmp(name, "embed_waste")) g_embed_waste = value;
+    else if (!strcmp(name, "scan_segments")) g_scan_segments = value;
+    else if (!strcmp(name, "scan_order")) g_scan_order = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 #include <vector>
@@ -14,6 +15,9 @@
 namespace ssam {
 
 // Launch parameters a caller may override through ssam_set_tuning (negative = built-in).
+// Scan overrides (ssam_set_tuning "scan_segments", "scan_order"); defined beside the scan kernels.
+extern std::atomic<int> g_scan_segments, g_scan_order;
+
 struct Tuning {
     int rows_per_wave = -1;    // 2D: output rows one wave marches over
     int valid_lanes = -1;      // lanes of a wave that store results (the rest are halo)

@@ -80,6 +80,38 @@ def test_tuning_names(L):
     assert L.ssam_set_tuning(b"no_such_knob", 1) == 4 and L.ssam_set_tuning(None, 1) == 1
 
 
+def test_scan_plan_and_validation(L):
+    """Workspace sizing and argument checks of ssam_scan; every call here fails validation (or is
+    empty) before anything is launched."""
+    vp = ctypes.c_void_p
+    ws = L.ssam_scan_workspace_bytes
+    assert ws(0, 0) == 0 and ws(-5, 0) == 0 and ws(1000, 9) == 0
+    assert ws(1024, 0) == 0 and ws(512, 1) == 0                 # one segment: no workspace
+    assert ws(1025, 0) == 16 and ws(513, 1) == 16               # two segments
+    assert ws(1 << 28, 0) == 8 * 32768 and ws(1 << 40, 1) == 8 * 32768
+    prev = 0
+    for n in (1 << 12, 1 << 16, 1 << 20, 1 << 24, 1 << 30):
+        cur = ws(n, 0)
+        assert prev <= cur <= 8 * 32768 and cur % 8 == 0
+        prev = cur
+    assert L.ssam_set_tuning(b"scan_segments", 5) == 0
+    assert ws(1 << 20, 0) == 40 and ws(1 << 20, 1) == 40
+    assert L.ssam_set_tuning(b"scan_segments", -1) == 0 and L.ssam_set_tuning(b"scan_order", -1) == 0
+    n = 1 << 20
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), 0, 0, None, 0, None) == 0          # empty: no-op
+    assert L.ssam_scan(None, None, 0, 1, None, 0, None) == 0
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), n, 2, vp(0x90000000), 1 << 18, None) == 4
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), -1, 0, vp(0x90000000), 1 << 18, None) == 2
+    assert L.ssam_scan(None, vp(FAKE_B), n, 0, vp(0x90000000), 1 << 18, None) == 1
+    assert L.ssam_scan(vp(FAKE_A), None, n, 0, vp(0x90000000), 1 << 18, None) == 1
+    assert L.ssam_scan(vp(FAKE_A + 2), vp(FAKE_B), n, 0, vp(0x90000000), 1 << 18, None) == 2
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_A + 4096), n, 0, vp(0x90000000), 1 << 18, None) == 5
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), n, 0, None, 0, None) == 1
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), n, 0, vp(0x90000000), ws(n, 0) - 1, None) == 2
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), n, 0, vp(0x90000004), 1 << 18, None) == 2
+    assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), n, 0, vp(FAKE_B + 64), 1 << 18, None) == 5
+
+
 def parse(desc):
     name, *kv = desc.split()
     out = {}

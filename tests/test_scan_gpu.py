@@ -1,0 +1,117 @@
+"""GPU parity of ssam_scan (inclusive prefix sums, Sec. 3.6) against the CPU oracle, element by
+element, through the C ABI.  Tolerance, per element i: |gpu_i - oracle_i| <= tol * (|a_0| + ... +
+|a_i|) with tol = 2e-6 for fp32 and 1e-13 for fp64.  It follows from the kernel's arithmetic: sums
+inside one step of 64 lanes are formed in the element type (at most 3 + 6 + 1 additions on the way
+to any output), everything carried across steps is fp64, and the result is rounded once."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_06154_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = {np.dtype(np.float32): 2e-6, np.dtype(np.float64): 1e-13}
+
+
+@pytest.fixture(scope="module")
+def ssam():
+    import paper_1907_06154_amd as s
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    s.lib()
+    yield s
+    for name in ("scan_segments", "scan_order"):
+        s.ssam_set_tuning(name, -1)
+
+
+def check(got, a, what):
+    want = oracle.scan(a)
+    bound = np.cumsum(np.abs(a.astype(np.float64)))
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    ratio = float(np.max(err / np.maximum(bound, np.finfo(np.float64).tiny))) if a.size else 0.0
+    assert ratio <= TOL[a.dtype], f"{what}: error / sum of magnitudes = {ratio:.3e}"
+
+
+SIZES = [1, 2, 3, 63, 64, 65, 127, 128, 255, 256, 257, 511, 1023, 1024, 1025, 2047, 4096, 4099,
+         65536, 100003, (1 << 20) + 17, (1 << 23) + 5]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_scan_matches_oracle(ssam, dtype):
+    for k, n in enumerate(SIZES):
+        lo = -1.0 if k % 2 == 0 else 0.0
+        a = wl.uniform_field((n,), lo, 1.0, 900 + k, dtype)
+        print(f"scan {np.dtype(dtype).name} n={n} range [{lo}, 1)", flush=True)
+        got = ssam.ssam_scan(torch.from_numpy(a).cuda())
+        torch.cuda.synchronize()
+        check(got.cpu().numpy(), a, f"n={n}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_scan_of_integers_is_exact(ssam, dtype):
+    """Small integers: every partial sum is an integer the element type holds, so any grouping of
+    the additions gives the same bits."""
+    n = (1 << 22) + 3
+    ones = torch.ones(n, dtype=torch.from_numpy(np.zeros(1, dtype)).dtype, device="cuda")
+    print(f"scan ones {np.dtype(dtype).name} n={n}", flush=True)
+    got = ssam.ssam_scan(ones)
+    torch.cuda.synchronize()
+    assert torch.equal(got, torch.arange(1, n + 1, device="cuda").to(got.dtype))
+    vals = (wl.uniform_field((n,), -4.0, 5.0, 921, np.float64)).astype(np.int64)
+    a = vals.astype(dtype)
+    got = ssam.ssam_scan(torch.from_numpy(a).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), np.cumsum(vals).astype(dtype))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_scan_segment_overrides_unaligned_and_in_place(ssam, dtype):
+    n = 300007
+    a = wl.uniform_field((n + 3,), -1.0, 1.0, 930, dtype)
+    for segs, order in [(1, -1), (3, 0), (7, 1), (100, 0), (4096, 1), (-1, 0)]:
+        ssam.ssam_set_tuning("scan_segments", segs)
+        ssam.ssam_set_tuning("scan_order", order)
+        print(f"scan {np.dtype(dtype).name} n={n} segments<={segs} order={order}", flush=True)
+        need = ssam.ssam_scan_workspace_bytes(n, dtype)
+        assert need <= 8 * (segs if segs > 0 else 32768) and (segs != 1 or need == 0)
+        d = torch.from_numpy(a).cuda()
+        # element-aligned only: input shifted by one element, output by three
+        out = torch.full((n + 3,), 7.0, dtype=d.dtype, device="cuda")
+        ssam.ssam_scan(d[1:n + 1], out[3:])
+        torch.cuda.synchronize()
+        assert float(out[0]) == 7.0 and float(out[2]) == 7.0
+        check(out[3:].cpu().numpy(), a[1:n + 1], f"unaligned, segments<={segs}")
+        # in place, with a workspace the caller owns
+        work = torch.empty(max(need, 8), dtype=torch.uint8, device="cuda")
+        x = d[:n].clone()
+        ssam.ssam_scan(x, x, work)
+        torch.cuda.synchronize()
+        check(x.cpu().numpy(), a[:n], f"in place, segments<={segs}")
+    ssam.ssam_set_tuning("scan_segments", -1)
+    ssam.ssam_set_tuning("scan_order", -1)
+
+
+def test_scan_edges_and_errors(ssam):
+    L = ssam.lib()
+    empty = torch.empty(0, dtype=torch.float32, device="cuda")
+    assert ssam.ssam_scan(empty).numel() == 0
+    a = torch.ones(1 << 16, dtype=torch.float32, device="cuda")
+    b = torch.zeros_like(a)
+    work = torch.empty(1 << 18, dtype=torch.uint8, device="cuda")
+    n, need = a.numel(), ssam.ssam_scan_workspace_bytes(a.numel(), torch.float32)
+    assert need > 0
+    p = lambda t, off=0: ctypes.c_void_p(t.data_ptr() + off)
+    assert L.ssam_scan(p(a), p(b), n, 0, p(work), need - 8, None) == 2       # workspace too small
+    assert L.ssam_scan(p(a), p(b), n, 0, None, 0, None) == 1                 # workspace missing
+    assert L.ssam_scan(p(a), p(b), n, 7, p(work), need, None) == 4           # dtype
+    assert L.ssam_scan(p(a), p(b), -1, 0, p(work), need, None) == 2
+    assert L.ssam_scan(p(a), p(a, 64), n - 16, 0, p(work), need, None) == 5  # partial overlap
+    assert L.ssam_scan(p(a), p(b), n, 0, p(a), need, None) == 5              # workspace inside the input
+    assert L.ssam_scan(p(a, 2), p(b), n - 1, 0, p(work), need, None) == 2    # misaligned element
+    assert L.ssam_scan(None, p(b), n, 0, p(work), need, None) == 1
+    torch.cuda.synchronize()
+    assert float(b.abs().sum()) == 0.0                                       # nothing was launched
