@@ -41,7 +41,9 @@ extern "C" {
 typedef enum {
     SSAM_OK = 0,
     SSAM_ERR_NULL = 1,   /* a required pointer is NULL                                    */
-    SSAM_ERR_DIM = 2,    /* W, H or D not positive, or the grid exceeds 2^31-1 elements   */
+    SSAM_ERR_DIM = 2,    /* W, H or D not positive, or the grid exceeds 2^31-1 elements;
+                            scan / probes: count out of range, misaligned pointer,
+                            scratch or workspace too small                                */
     SSAM_ERR_SHAPE = 3,  /* filter / radius not positive, anchor outside the filter, or
                             larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0; a
                             dense coefficient box too large for any kernel (ssam_stencil3d) */
@@ -114,8 +116,12 @@ const char *ssam_status_string(int status);
  * "embed_waste" (a 2D filter shape without a compiled instance runs inside the smallest compiled
  * square box that holds it, zero-padded; a value n >= 0 allows that only while the box has at most
  * n times its taps, 0 = never: such shapes then use the direct one-point-per-thread kernel),
- * "scan_segments" (ssam_scan: upper limit of segments, 1 .. 32768; ssam_scan_workspace_bytes
- * follows it), "scan_order" (0 = the last launch of ssam_scan takes the segments first to last).
+ * "scan_segments" (ssam_scan, three-launch schedule: upper limit of segments, 1 .. 4096),
+ * "scan_order" (0 = its last launch takes the segments first to last), "scan_chained" (0 = never
+ * the one-pass schedule, 1 = for every out-of-place array it can hold; built-in: from 128 MiB),
+ * "scan_spin_limit" (polls a waiting wave of the one-pass schedule makes before it gives up, at
+ * most 2^20; 0 makes every wave that would wait give up at once -- a test of the redo path);
+ * ssam_scan_workspace_bytes follows these.
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
 
@@ -138,20 +144,32 @@ int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int 
  * size (16-byte alignment of both selects the vector-access kernels); d_out may be the same
  * pointer as d_in (in place), any other overlap gives SSAM_ERR_ALIAS.  d_work: device
  * workspace of at least ssam_scan_workspace_bytes(n, dtype) bytes, 8-byte aligned, not
- * overlapping the arrays, owned by the caller and free for reuse once the call's work on
- * hip_stream has finished; it may be NULL when that size is 0 (short arrays).  The array is
- * cut into contiguous segments, one per wave; three launches are enqueued on hip_stream (segment
- * sums, their exclusive prefixes, the scan of every segment) and the call returns without
- * waiting and without allocating.  Totals that cross a 64-lane step are carried in fp64 for both
- * element types, so the fp32 result is within a few fp32 roundings of the exact prefix, relative
- * to the sum of magnitudes.  n == 0 is a no-op.  Errors: SSAM_ERR_ENUM (dtype), SSAM_ERR_DIM
- * (n < 0, misaligned pointer, workspace too small), SSAM_ERR_NULL, SSAM_ERR_ALIAS, SSAM_ERR_HIP. */
+ * overlapping the arrays, owned by the caller, contents irrelevant on entry, free for reuse once
+ * the call's work on hip_stream has finished (two calls in flight must not share one); it may be
+ * NULL when that size is 0 (short arrays).  The call enqueues its launches on hip_stream and
+ * returns without waiting and without allocating; no memset is enqueued, so it can be captured.
+ * Two schedules, chosen by size:
+ *   - three launches (below 128 MiB, and always in place): the array is cut into contiguous
+ *     segments, one per wave; segment sums, their exclusive prefixes, the scan of every segment
+ *     (2 reads + 1 write per element);
+ *   - one pass (from 128 MiB, out of place, up to 2^30 fp32 / 2^29 fp64 elements): every wave
+ *     keeps a segment in registers, publishes its sum in the workspace and combines the sums of
+ *     the waves before it, always in the same order (1 read + 1 write per element, results
+ *     reproducible run to run).  Waves take segments from a ticket counter, so they only wait
+ *     for waves already running, and every wait is bounded: if a wave runs out of polls (a
+ *     device shared with other work) it raises a flag, 8-byte word 16 of the workspace, and the
+ *     three launches, enqueued behind the pass and gated on that flag, redo the array.
+ * Totals that cross a 64-lane step are carried in fp64 for both element types, so the result is
+ * within a few roundings of the element type of the exact prefix, relative to the sum of
+ * magnitudes.  A non-finite partial sum makes the later results non-finite (an infinity may read
+ * as NaN).  n == 0 is a no-op.  Errors: SSAM_ERR_ENUM (dtype), SSAM_ERR_DIM (n < 0 or above
+ * 2^40, misaligned pointer, workspace too small), SSAM_ERR_NULL, SSAM_ERR_ALIAS, SSAM_ERR_HIP. */
 int ssam_scan(const void *d_in, void *d_out, long long n, int dtype,
               void *d_work, size_t work_bytes, void *hip_stream);
 
 /* Host only: bytes of workspace ssam_scan needs for n elements of dtype under the current
- * tuning (8 bytes per segment, at most 256 KiB; 0 when one segment suffices or the arguments
- * are invalid). */
+ * tuning, whichever schedule the pointers then select (at most about 2.1 MiB; 0 when one segment
+ * suffices or the arguments are invalid). */
 size_t ssam_scan_workspace_bytes(long long n, int dtype);
 
 /* Measurement aid: copies nbytes (a multiple of 16; both pointers 16-byte aligned, not

@@ -546,7 +546,7 @@ const char* ssam_status_string(int status)
     switch (status) {
         case SSAM_OK: return "ok";
         case SSAM_ERR_NULL: return "null pointer argument";
-        case SSAM_ERR_DIM: return "grid dimension not positive or grid too large";
+        case SSAM_ERR_DIM: return "size out of range (grid dimension, element count), misaligned pointer or workspace too small";
         case SSAM_ERR_SHAPE: return "filter, radius, anchor or step count out of range";
         case SSAM_ERR_ENUM: return "unknown dtype, boundary or tuning name";
         case SSAM_ERR_ALIAS: return "input and output buffers overlap";
@@ -569,6 +569,8 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "embed_waste")) g_embed_waste = value;
     else if (!strcmp(name, "scan_segments")) g_scan_segments = value;
     else if (!strcmp(name, "scan_order")) g_scan_order = value;
+    else if (!strcmp(name, "scan_chained")) g_scan_chained = value;
+    else if (!strcmp(name, "scan_spin_limit")) g_scan_spin_limit = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

@@ -92,7 +92,7 @@ def tune_scan(ssam, wl, torch, case: str, keys, vals, reps: int) -> int:
     dt = torch.float32 if tag == "f32" else torch.float64
     a = wl.uniform_field_on("cuda", (n,), -1.0, 1.0, 11, np.float32 if tag == "f32" else np.float64)
     b = torch.empty_like(a)
-    work = torch.empty(1 << 18, dtype=torch.uint8, device="cuda")
+    work = torch.empty(8 << 20, dtype=torch.uint8, device="cuda")   # above the largest workspace of any schedule
     esz = a.element_size()
 
     def run():

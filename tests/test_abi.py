@@ -88,15 +88,17 @@ def test_scan_plan_and_validation(L):
     assert ws(0, 0) == 0 and ws(-5, 0) == 0 and ws(1000, 9) == 0
     assert ws(1024, 0) == 0 and ws(512, 1) == 0                 # one segment: no workspace
     assert ws(1025, 0) == 16 and ws(513, 1) == 16               # two segments
-    assert ws(1 << 28, 0) == 8 * 32768 and ws(1 << 40, 1) == 8 * 32768
-    prev = 0
-    for n in (1 << 12, 1 << 16, 1 << 20, 1 << 24, 1 << 30):
-        cur = ws(n, 0)
-        assert prev <= cur <= 8 * 32768 and cur % 8 == 0
-        prev = cur
-    assert L.ssam_set_tuning(b"scan_segments", 5) == 0
-    assert ws(1 << 20, 0) == 40 and ws(1 << 20, 1) == 40
-    assert L.ssam_set_tuning(b"scan_segments", -1) == 0 and L.ssam_set_tuning(b"scan_order", -1) == 0
+    # arrays of 128 MiB and more, up to 64^3 register-resident segments of 16 KiB: the one-pass schedule
+    # (ticket and flag, 64 padded + 4096 + one per segment published sums of 8 bytes, 4096 sums for the
+    # gated launches); the three launches use at most 4096 segments
+    one_pass = lambda segs: 8 * (32 + 16 * 64 + 4096 + segs + 4096)
+    assert ws((1 << 25) - 1, 0) == 8 * 4096 and ws(1 << 25, 0) == one_pass(1 << 13)
+    assert ws(1 << 28, 0) == one_pass(1 << 16) and ws(1 << 28, 1) == one_pass(1 << 17)
+    assert ws(1 << 30, 0) == one_pass(1 << 18) and 8 * 4000 < ws((1 << 30) + 1, 0) <= 8 * 4096
+    assert ws(1 << 40, 1) == 8 * 4096 and ws((1 << 40) + 1, 1) == 0
+    assert L.ssam_set_tuning(b"scan_chained", 0) == 0 and ws(1 << 28, 0) == 8 * 4096
+    assert L.ssam_set_tuning(b"scan_chained", 1) == 0 and ws(5000, 0) == one_pass(2)
+    assert L.ssam_set_tuning(b"scan_chained", -1) == 0 and L.ssam_set_tuning(b"scan_spin_limit", -1) == 0
     n = 1 << 20
     assert L.ssam_scan(vp(FAKE_A), vp(FAKE_B), 0, 0, None, 0, None) == 0          # empty: no-op
     assert L.ssam_scan(None, None, 0, 1, None, 0, None) == 0

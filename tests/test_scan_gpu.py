@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
+KNOBS = ("scan_segments", "scan_order", "scan_chained", "scan_spin_limit")
 TOL = {np.dtype(np.float32): 2e-6, np.dtype(np.float64): 1e-13}
 
 
@@ -24,7 +25,7 @@ def ssam():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     s.lib()
     yield s
-    for name in ("scan_segments", "scan_order"):
+    for name in KNOBS:
         s.ssam_set_tuning(name, -1)
 
 
@@ -73,11 +74,12 @@ def test_scan_segment_overrides_unaligned_and_in_place(ssam, dtype):
     n = 300007
     a = wl.uniform_field((n + 3,), -1.0, 1.0, 930, dtype)
     for segs, order in [(1, -1), (3, 0), (7, 1), (100, 0), (4096, 1), (-1, 0)]:
+        ssam.ssam_set_tuning("scan_chained", 0)
         ssam.ssam_set_tuning("scan_segments", segs)
         ssam.ssam_set_tuning("scan_order", order)
         print(f"scan {np.dtype(dtype).name} n={n} segments<={segs} order={order}", flush=True)
         need = ssam.ssam_scan_workspace_bytes(n, dtype)
-        assert need <= 8 * (segs if segs > 0 else 32768) and (segs != 1 or need == 0)
+        assert need <= 8 * (segs if segs > 0 else 4096) and (segs != 1 or need == 0)
         d = torch.from_numpy(a).cuda()
         # element-aligned only: input shifted by one element, output by three
         out = torch.full((n + 3,), 7.0, dtype=d.dtype, device="cuda")
@@ -91,8 +93,126 @@ def test_scan_segment_overrides_unaligned_and_in_place(ssam, dtype):
         ssam.ssam_scan(x, x, work)
         torch.cuda.synchronize()
         check(x.cpu().numpy(), a[:n], f"in place, segments<={segs}")
-    ssam.ssam_set_tuning("scan_segments", -1)
-    ssam.ssam_set_tuning("scan_order", -1)
+        # in place never takes the one-pass schedule, also when it is forced for the size
+        ssam.ssam_set_tuning("scan_chained", 1)
+        x = d[:n].clone()
+        ssam.ssam_scan(x, x)
+        torch.cuda.synchronize()
+        check(x.cpu().numpy(), a[:n], f"in place with one pass requested, segments<={segs}")
+    for name in KNOBS:
+        ssam.ssam_set_tuning(name, -1)
+
+
+def gave_up(work) -> int:
+    """Word 16 of the workspace of a one-pass call: nonzero if a wave ran out of polls and the
+    gated launches redid the array."""
+    torch.cuda.synchronize()
+    return int(work.view(torch.int64)[16])
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_one_pass_scan_matches_oracle(ssam, dtype):
+    """The one-pass schedule, forced on short arrays too: one segment, ragged last segments, several
+    groups of 64 segments, and more than 64 groups (the third level of published sums)."""
+    short = 16 * 64 * (4 if dtype == np.float32 else 2)   # segment with element-wise accesses; 16-byte accesses: twice that
+    per = 2 * short
+    ssam.ssam_set_tuning("scan_chained", 1)
+    sizes = [1, per - 1, per, per + 1, 5 * per + 77, 64 * per, 64 * per + 1, 200 * per + 13, 4100 * per + 3]
+    for k, n in enumerate(sizes):
+        a = wl.uniform_field((n + 1,), -1.0, 1.0, 950 + k, dtype)
+        need = ssam.ssam_scan_workspace_bytes(n, dtype)
+        assert need >= 8 * (5152 + -(-n // short))
+        work = torch.empty(need, dtype=torch.uint8, device="cuda")
+        d = torch.from_numpy(a).cuda()
+        for off in (0, 1):                       # 16-byte aligned, then element-aligned only
+            print(f"one-pass scan {np.dtype(dtype).name} n={n} offset={off}", flush=True)
+            out = torch.empty(n + 1, dtype=d.dtype, device="cuda")
+            ssam.ssam_scan(d[off:off + n], out[off:off + n], work)
+            assert gave_up(work) == 0
+            check(out[off:off + n].cpu().numpy(), a[off:off + n], f"one pass n={n} offset={off}")
+    # by default arrays of 128 MiB and more take the one-pass schedule, shorter ones do not
+    ssam.ssam_set_tuning("scan_chained", -1)
+    n = (160 << 20) // np.dtype(dtype).itemsize + 3
+    assert ssam.ssam_scan_workspace_bytes(n, dtype) >= 8 * (5152 + n // short)
+    assert ssam.ssam_scan_workspace_bytes(n // 2, dtype) <= 8 * 4096
+    a = wl.uniform_field((n,), 0.0, 1.0, 970, dtype)
+    got = ssam.ssam_scan(torch.from_numpy(a).cuda())
+    torch.cuda.synchronize()
+    check(got.cpu().numpy(), a, "one pass by default")
+    # twice the same bits: the sums are combined in a fixed order whatever the timing
+    again = ssam.ssam_scan(torch.from_numpy(a).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_one_pass_scan_that_gives_up_is_redone(ssam, dtype):
+    """A poll limit of 0 set from the host makes every wave that would have to wait give up at
+    once (no wave spins); the launches gated on the flag then produce the result."""
+    per = 32 * 64 * (4 if dtype == np.float32 else 2)
+    n = 300 * per + 5
+    a = wl.uniform_field((n,), -1.0, 1.0, 980, dtype)
+    ssam.ssam_set_tuning("scan_chained", 1)
+    ssam.ssam_set_tuning("scan_spin_limit", 0)
+    work = torch.empty(ssam.ssam_scan_workspace_bytes(n, dtype), dtype=torch.uint8, device="cuda")
+    print(f"one-pass scan with poll limit 0, {np.dtype(dtype).name} n={n}", flush=True)
+    got = ssam.ssam_scan(torch.from_numpy(a).cuda(), None, work)
+    assert gave_up(work) == 1
+    check(got.cpu().numpy(), a, "redone after giving up")
+    ssam.ssam_set_tuning("scan_spin_limit", -1)
+    got = ssam.ssam_scan(torch.from_numpy(a).cuda(), None, work)
+    assert gave_up(work) == 0
+    check(got.cpu().numpy(), a, "same workspace, normal limit")
+    ssam.ssam_set_tuning("scan_chained", -1)
+
+
+@pytest.mark.parametrize("chained", [0, 1])
+def test_scan_can_be_captured_in_a_hip_graph(ssam, chained):
+    """Both schedules only enqueue kernels on the caller's stream (the workspace is cleared by a
+    kernel, not a memset), so a call can be captured and replayed; every replay is checked against
+    the eager result, with eager work and synchronisations in between."""
+    n = 3_000_017
+    a = wl.uniform_field((n,), -1.0, 1.0, 990, np.float32)
+    ssam.ssam_set_tuning("scan_chained", chained)
+    d = torch.from_numpy(a).cuda()
+    out = torch.empty_like(d)
+    work = torch.empty(ssam.ssam_scan_workspace_bytes(n, np.float32), dtype=torch.uint8, device="cuda")
+    ssam.ssam_scan(d, out, work)
+    torch.cuda.synchronize()
+    eager = out.cpu().numpy().copy()
+    check(eager, a, "eager")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ssam.ssam_scan(d, out, work)
+    for replay in range(4):
+        print(f"scan graph replay {replay}, one pass {chained}", flush=True)
+        out.fill_(float("nan"))
+        work.fill_(255)                         # whatever the workspace holds is cleared by the call
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), eager), f"replay {replay} differs from the eager run"
+        other = ssam.ssam_scan(d[: n // 3])      # unrelated eager work between replays
+        torch.cuda.synchronize()
+        check(other.cpu().numpy(), a[: n // 3], "eager between replays")
+    ssam.ssam_set_tuning("scan_chained", -1)
+
+
+def test_scan_of_a_gibibyte(ssam):
+    """2^28 fp32 elements, generated on the device with the shared counter-based generator, the
+    default (one-pass) schedule, every element against the oracle."""
+    n = 1 << 28
+    d = wl.uniform_field_on("cuda", (n,), -1.0, 1.0, 995, np.float32)
+    print(f"scan f32 n={n}", flush=True)
+    work = torch.empty(ssam.ssam_scan_workspace_bytes(n, np.float32), dtype=torch.uint8, device="cuda")
+    got = ssam.ssam_scan(d, None, work)
+    assert gave_up(work) == 0
+    a = d.cpu().numpy()
+    want = oracle.scan(a)
+    bound = np.cumsum(np.abs(a), dtype=np.float64)
+    err = np.abs(got.cpu().numpy().astype(np.float64) - want)
+    assert float(np.max(err / np.maximum(bound, 1e-300))) <= TOL[np.dtype(np.float32)]
 
 
 def test_scan_edges_and_errors(ssam):
