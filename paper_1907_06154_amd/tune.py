@@ -120,9 +120,19 @@ def tune_scan(ssam, wl, torch, case: str, keys, vals, reps: int) -> int:
         ms = e0.elapsed_time(e1) / reps
         knobs = " ".join(f"{k}={v}" for k, v in zip(keys, combo))
         print(f"scan {tag} n={n} {knobs}  {ms * 1e3:8.1f} us {n / ms / 1e6:7.1f} Gelem/s {2 * esz * n / ms / 1e6:7.0f} GB/s "
-              f"({ssam.ssam_scan_workspace_bytes(n, dt) // 8} segments)", flush=True)
+              f"(workspace {ssam.ssam_scan_workspace_bytes(n, dt)} B)", flush=True)
     for k in keys:
         ssam.ssam_set_tuning(k, -1)
+    # the ceiling for one read and one write per element: the plain copy kernel on the same arrays
+    for _ in range(2):
+        ssam.ssam_probe_copy(a, b)
+    e0.record()
+    for _ in range(reps):
+        ssam.ssam_probe_copy(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    print(f"copy {tag} n={n}  {ms * 1e3:8.1f} us {n / ms / 1e6:7.1f} Gelem/s {2 * esz * n / ms / 1e6:7.0f} GB/s", flush=True)
     return 0
 
 
