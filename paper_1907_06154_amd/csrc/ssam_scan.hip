@@ -59,10 +59,18 @@ constexpr int kOffsetsThreads = 1024;    // the one workgroup of launch 2 ...
 constexpr int kOffsetsEach = kScanMaxSegments / kOffsetsThreads;   // ... and the sums one of its threads owns
 
 // One-pass schedule.
-// Wave-rounds a wave holds in registers: 32 KiB per segment with 16-byte accesses (about 250
-// registers, two waves per SIMD -- fewer, longer segments measured faster than more waves), 16 KiB
-// with element-wise accesses.  The workspace is sized for the shorter segments.
-constexpr int kChainRoundsAligned = 32, kChainRoundsUnaligned = 16;
+// Wave-rounds a wave holds in registers: with 16-byte accesses 32 KiB per segment for fp32 and
+// 26 KiB for fp64 (the most that fits 256 registers, two waves per SIMD -- fewer, longer segments
+// measured faster than more waves), 16 KiB with element-wise accesses.  The workspace is sized for
+// the shortest segments.
+#if !defined(SSAM_SCAN_ROUNDS_F64)
+#define SSAM_SCAN_ROUNDS_F64 26
+#endif
+constexpr int kChainRoundsUnaligned = 16;
+constexpr int chain_rounds(int dtype, bool aligned)
+{
+    return !aligned ? kChainRoundsUnaligned : dtype == SSAM_F32 ? 32 : SSAM_SCAN_ROUNDS_F64;
+}
 constexpr int kChainFan = 64;                                      // items summed per level = lanes
 constexpr long long kChainMaxSegments = 64LL * 64 * 64;            // three levels
 constexpr int kChainRedoSegments = 4096;                           // segments of the gated three launches
@@ -306,7 +314,7 @@ template <class T, bool ALIGNED>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) void scan_chained(const T* __restrict__ a, T* __restrict__ b, Word* ws, ChainPlan pl)
 {
     constexpr int V = ScanVec<T>::V;
-    constexpr int kChainRounds = ALIGNED ? kChainRoundsAligned : kChainRoundsUnaligned;
+    constexpr int kChainRounds = chain_rounds(sizeof(T) == 4 ? SSAM_F32 : SSAM_F64, ALIGNED);
     __shared__ unsigned ticket;
     if (threadIdx.x == 0)
         ticket = __hip_atomic_fetch_add(reinterpret_cast<unsigned*>(ws + kWsTicket), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -340,6 +348,22 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
 #if defined(SSAM_SCAN_STATS)
     const long long c_loaded = wall_clock64();
 #endif
+
+    // The scan inside the segment, while the sums of the earlier waves arrive: afterwards v holds
+    // every element's prefix within its wave-round, and lane k the sum of the rounds before round k.
+    double round_total = 0.0;
+#pragma unroll
+    for (int k = 0; k < kChainRounds; ++k) {
+#pragma unroll
+        for (int j = 1; j < V; ++j) v[k][j] += v[k][j - 1];
+        const T incl = wave_inclusive_scan(v[k][V - 1]);
+        const T before = shift_up(incl);
+#pragma unroll
+        for (int j = 0; j < V; ++j) v[k][j] += before;
+        const double t = (double)read_lane(incl, kWave - 1);
+        if (lane == k) round_total = t;
+    }
+    const double round_start = shift_up(wave_inclusive_scan(round_total));
 
     // What lies before the segment, one item per lane and kind:
     //   mine_[l] = A[64 g + l], l < i         the earlier segments of the group
@@ -396,18 +420,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     const long long c_waited = wall_clock64();
 #endif
 
-    double carry = before_group + sum_mine;
+    // only the start value is missing now: add it, round once, store
+    const double start = before_group + sum_mine;
 #pragma unroll
     for (int k = 0; k < kChainRounds; ++k) {
-#pragma unroll
-        for (int j = 1; j < V; ++j) v[k][j] += v[k][j - 1];
-        const T incl = wave_inclusive_scan(v[k][V - 1]);
-        const T before = shift_up(incl);
+        const double c = start + read_lane(round_start, k);
         T o[V];
 #pragma unroll
-        for (int j = 0; j < V; ++j) o[j] = (T)(carry + (double)(before + v[k][j]));
+        for (int j = 0; j < V; ++j) o[j] = (T)(c + (double)v[k][j]);
         store_elems<T, ALIGNED>(b, e0 + (long long)k * kWave * V, pl.n, o);
-        carry += (double)read_lane(incl, kWave - 1);
     }
 #if defined(SSAM_SCAN_STATS)
     // Diagnostic build only (the workspace must then be at least 16 MiB): per segment, the
@@ -532,7 +553,7 @@ int ssam_scan(const void* d_in, void* d_out, long long n, int dtype, void* d_wor
     const size_t bytes = (size_t)n * esz;
     if (pa != pb && pa < pb + bytes && pb < pa + bytes) return SSAM_ERR_ALIAS;   // in place is fine, a partial overlap is not
     const bool aligned = pa % 16 == 0 && pb % 16 == 0;
-    const long long chain_segs = pa == pb ? 0 : chained_segments(n, dtype, aligned ? kChainRoundsAligned : kChainRoundsUnaligned);
+    const long long chain_segs = pa == pb ? 0 : chained_segments(n, dtype, chain_rounds(dtype, aligned));
     const size_t need = chain_segs ? chained_bytes(chained_segments(n, dtype, kChainRoundsUnaligned)) : three_launch_bytes(n, dtype);
     if (need) {
         if (!d_work) return SSAM_ERR_NULL;

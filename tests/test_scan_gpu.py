@@ -114,8 +114,8 @@ def gave_up(work) -> int:
 def test_one_pass_scan_matches_oracle(ssam, dtype):
     """The one-pass schedule, forced on short arrays too: one segment, ragged last segments, several
     groups of 64 segments, and more than 64 groups (the third level of published sums)."""
-    short = 16 * 64 * (4 if dtype == np.float32 else 2)   # segment with element-wise accesses; 16-byte accesses: twice that
-    per = 2 * short
+    short = 16 * 64 * (4 if dtype == np.float32 else 2)   # segment with element-wise accesses (16 wave-rounds)
+    per = (32 * 64 * 4) if dtype == np.float32 else (26 * 64 * 2)   # with 16-byte accesses: 32 or 26 wave-rounds
     ssam.ssam_set_tuning("scan_chained", 1)
     sizes = [1, per - 1, per, per + 1, 5 * per + 77, 64 * per, 64 * per + 1, 200 * per + 13, 4100 * per + 3]
     for k, n in enumerate(sizes):
@@ -149,7 +149,7 @@ def test_one_pass_scan_matches_oracle(ssam, dtype):
 def test_one_pass_scan_that_gives_up_is_redone(ssam, dtype):
     """A poll limit of 0 set from the host makes every wave that would have to wait give up at
     once (no wave spins); the launches gated on the flag then produce the result."""
-    per = 32 * 64 * (4 if dtype == np.float32 else 2)
+    per = (32 * 64 * 4) if dtype == np.float32 else (26 * 64 * 2)
     n = 300 * per + 5
     a = wl.uniform_field((n,), -1.0, 1.0, 980, dtype)
     ssam.ssam_set_tuning("scan_chained", 1)
