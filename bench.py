@@ -144,7 +144,7 @@ def main() -> int:
 
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1. "
-              "DESIGN.md describes how the path would shard.", file=sys.stderr)
+              "Across GPUs the path would shard by slabs along the slowest axis with a halo exchange between neighbours.", file=sys.stderr)
         return 2
 
     import torch
