@@ -129,12 +129,76 @@ def cpu_baseline(cases, target_seconds: float):
                       f"({', '.join(desc)}; {pts} points, {secs:.1f} s of oracle time)"}
 
 
+# HBM bytes one ssam_scan call moves at the benchmark size (one-pass schedule), from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE counters scaled by the copy kernel's readings (profiles/scan_1GiB_f32_f64.md)
+SCAN_MEASURED_TRAFFIC_BYTES = {"f32": int((1027.2 + 1025.3) * 2 ** 20), "f64": int((1027.1 + 1025.6) * 2 ** 20)}
+
+
+def bench_scan(ssam, wl, torch, args) -> int:
+    """The scan mapping of the model (paper Sec. 3.6; not evaluated there): inclusive prefix sums of
+    1 GiB arrays, fp32 then fp64, one call each per step; elements per second, with the roofline of
+    the fp32 call (one read and one write per element are the algorithmic bytes)."""
+    steps = args.steps if args.steps is not None else 20
+    warmup = args.warmup if args.warmup is not None else 3
+    nbytes = 1 << 30
+    arrays = {}
+    for tag, dt in (("f32", np.float32), ("f64", np.float64)):
+        n = nbytes // np.dtype(dt).itemsize
+        a = wl.uniform_field_on("cuda", (n,), -1.0, 1.0, 11, dt)
+        work = torch.empty(ssam.ssam_scan_workspace_bytes(n, dt), dtype=torch.uint8, device="cuda")
+        arrays[tag] = (a, torch.empty_like(a), work)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        for a, b, work in arrays.values():
+            ssam.ssam_scan(a, b, work)
+    torch.cuda.synchronize()
+    ev = {tag: [] for tag in arrays}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for tag, (a, b, work) in arrays.items():
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record(stream)
+            ssam.ssam_scan(a, b, work)
+            e.record(stream)
+            ev[tag].append((s, e))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernels, elems = [], 0
+    for tag, (a, b, work) in arrays.items():
+        ms = float(np.mean([s.elapsed_time(e) for s, e in ev[tag]]))
+        gbps = 2 * nbytes / (ms * 1e-3) / 1e9
+        kernels.append({"case": f"scan_{tag}_1GiB", "call_ms": ms, "gelem_per_s": a.numel() / ms / 1e6, "hbm_GBps": gbps,
+                        "hbm_frac": gbps / HBM_PEAK_GBPS, "traffic": SCAN_MEASURED_TRAFFIC_BYTES[tag],
+                        "redone_after_giving_up": int(work.view(torch.int64)[16])})
+        elems += a.numel()
+    dom = kernels[0]
+    out = {"metric": "Gelem/s", "value": elems / (wall / steps) / 1e9, "unit": "Gelem/s", "n_gpus": 1, "steps": steps,
+           "warmup": warmup, "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32+f64", "data": "synthetic",
+           "config": {"workload": "scan: inclusive prefix sums of 2^28 fp32 and 2^27 fp64 elements (1 GiB each), out of place"},
+           "roofline": {"bound": "hbm", "achieved": dom["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": dom["hbm_frac"], "traffic": dom["traffic"], "kernel": "scan_chained<float>", "case": dom["case"]},
+           "kernels": kernels}
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = arrays["f32"][0][: 1 << 26].cpu().numpy()
+        reps, t1 = 0, time.perf_counter()
+        while time.perf_counter() - t1 < min(args.cpu_seconds, 10.0):
+            oracle.scan(sample)
+            reps += 1
+        dt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": reps * sample.size / dt / 1e9, "unit": "Gelem/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first 2^26 fp32 elements of the same array, {reps} passes, {dt:.1f} s (the oracle's scan is sequential)"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "filter_sweep", "table3"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "filter_sweep", "table3", "scan"])
     ap.add_argument("--cases", default=None, help="comma-separated substrings selecting cases of the workload")
     ap.add_argument("--fuse-sweeps", type=int, default=-1,
                     help="cap on the sweeps ssam_stencil_iterate fuses into one launch (0: none; default: the library's choice)")
@@ -158,6 +222,9 @@ def main() -> int:
     ssam.lib()
     torch.cuda.set_device(0)
     ssam.ssam_set_tuning("fuse_sweeps", args.fuse_sweeps)
+
+    if args.workload == "scan":
+        return bench_scan(ssam, wl, torch, args)
 
     cases = wl.all_configs()[args.workload]
     if args.cases:
