@@ -199,6 +199,30 @@ def test_scan_can_be_captured_in_a_hip_graph(ssam, chained):
     ssam.ssam_set_tuning("scan_chained", -1)
 
 
+def test_one_pass_scans_on_two_streams_at_once(ssam):
+    """Two one-pass scans in flight on their own streams with their own workspaces: the waves of one
+    only ever wait for waves of the same launch that already run, so sharing the device costs time,
+    not correctness; neither gives up."""
+    n = (96 << 20) // 4 + 11
+    ssam.ssam_set_tuning("scan_chained", 1)
+    jobs = []
+    for k, dtype in enumerate((np.float32, np.float64)):
+        a = wl.uniform_field((n // (k + 1),), -1.0, 1.0, 985 + k, dtype)
+        d = torch.from_numpy(a).cuda()
+        work = torch.empty(ssam.ssam_scan_workspace_bytes(a.size, dtype), dtype=torch.uint8, device="cuda")
+        jobs.append((a, d, torch.empty_like(d), work, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(6):
+        print(f"two streams, repetition {rep}", flush=True)
+        for a, d, out, work, st in jobs:
+            ssam.ssam_scan(d, out, work, stream=st)
+    torch.cuda.synchronize()
+    for a, d, out, work, st in jobs:
+        assert gave_up(work) == 0
+        check(out.cpu().numpy(), a, f"two streams, {a.dtype}")
+    ssam.ssam_set_tuning("scan_chained", -1)
+
+
 def test_scan_of_a_gibibyte(ssam):
     """2^28 fp32 elements, generated on the device with the shared counter-based generator, the
     default (one-pass) schedule, every element against the oracle."""
