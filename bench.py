@@ -131,7 +131,7 @@ def cpu_baseline(cases, target_seconds: float):
 
 # HBM bytes one ssam_scan call moves at the benchmark size (one-pass schedule), from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE counters scaled by the copy kernel's readings (profiles/scan_1GiB_f32_f64.md)
-SCAN_MEASURED_TRAFFIC_BYTES = {"f32": int((1027.2 + 1025.3) * 2 ** 20), "f64": int((1027.1 + 1025.6) * 2 ** 20)}
+SCAN_MEASURED_TRAFFIC_BYTES = {"f32": int((1027.0 + 1026.4) * 2 ** 20), "f64": int((1027.0 + 1026.3) * 2 ** 20)}
 
 
 def bench_scan(ssam, wl, torch, args) -> int:

@@ -119,35 +119,31 @@ __device__ __forceinline__ T wave_inclusive_scan(T x)
     return x;
 }
 
-template <class T> struct ScanVec;
-template <> struct ScanVec<float> { using type = float4; static constexpr int V = 4; };
-template <> struct ScanVec<double> { using type = double2; static constexpr int V = 2; };
+// 16 bytes per lane.
+template <class T> struct ScanVec { static constexpr int V = 16 / sizeof(T); };
 
 // Elements [i, i + V) of a, zeros past n.  ALIGNED: the base pointer is 16-byte aligned, so a
-// vector that lies wholly inside the array is one 16-byte access.
-template <class T, bool ALIGNED>
+// vector that lies wholly inside the array is one 16-byte access.  STREAM: non-temporal access --
+// the one-pass schedule, whose arrays are far larger than the caches, gains 6 % from it; the three
+// launches keep plain accesses, their second read of a mid-sized array comes from the caches.
+template <class T, bool ALIGNED, bool STREAM = false>
 __device__ __forceinline__ void load_elems(const T* __restrict__ a, long long i, long long n, T (&v)[ScanVec<T>::V])
 {
     constexpr int V = ScanVec<T>::V;
     if (ALIGNED && i + V <= n) {
-        const typename ScanVec<T>::type q = *reinterpret_cast<const typename ScanVec<T>::type*>(a + i);
-        if constexpr (V == 4) { v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w; }
-        else { v[0] = q.x; v[1] = q.y; }
+        load_vec<T, V, STREAM>(a + i, v);
     } else {
 #pragma unroll
         for (int j = 0; j < V; ++j) v[j] = (i + j < n) ? a[i + j] : T(0);
     }
 }
 
-template <class T, bool ALIGNED>
+template <class T, bool ALIGNED, bool STREAM = false>
 __device__ __forceinline__ void store_elems(T* __restrict__ b, long long i, long long n, const T (&v)[ScanVec<T>::V])
 {
     constexpr int V = ScanVec<T>::V;
     if (ALIGNED && i + V <= n) {
-        typename ScanVec<T>::type q;
-        if constexpr (V == 4) { q.x = v[0]; q.y = v[1]; q.z = v[2]; q.w = v[3]; }
-        else { q.x = v[0]; q.y = v[1]; }
-        *reinterpret_cast<typename ScanVec<T>::type*>(b + i) = q;
+        store_vec<T, V, STREAM>(b + i, v);
     } else {
 #pragma unroll
         for (int j = 0; j < V; ++j)
@@ -329,7 +325,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     T v[kChainRounds][V];
     const long long e0 = (s * kChainRounds * kWave + lane) * V;
 #pragma unroll
-    for (int k = 0; k < kChainRounds; ++k) load_elems<T, ALIGNED>(a, e0 + (long long)k * kWave * V, pl.n, v[k]);
+    for (int k = 0; k < kChainRounds; ++k) load_elems<T, ALIGNED, true>(a, e0 + (long long)k * kWave * V, pl.n, v[k]);
 
     // the segment's sum, published before anything is waited for
     double mine = 0.0;
@@ -428,7 +424,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         T o[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) o[j] = (T)(c + (double)v[k][j]);
-        store_elems<T, ALIGNED>(b, e0 + (long long)k * kWave * V, pl.n, o);
+        store_elems<T, ALIGNED, true>(b, e0 + (long long)k * kWave * V, pl.n, o);
     }
 #if defined(SSAM_SCAN_STATS)
     // Diagnostic build only (the workspace must then be at least 16 MiB): per segment, the
