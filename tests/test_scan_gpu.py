@@ -199,6 +199,30 @@ def test_scan_can_be_captured_in_a_hip_graph(ssam, chained):
     ssam.ssam_set_tuning("scan_chained", -1)
 
 
+def test_scan_random_sizes_offsets_and_schedules(ssam):
+    """Seeded random lengths, element offsets of input and output, segment limits and schedules."""
+    rng = np.random.default_rng(20240607)
+    pool = {dt: wl.uniform_field((3_000_000 + 8,), -1.0, 1.0, 960 + k, dt) for k, dt in enumerate((np.float32, np.float64))}
+    dev_pool = {dt: torch.from_numpy(a).cuda() for dt, a in pool.items()}
+    for case in range(48):
+        dt = (np.float32, np.float64)[case % 2]
+        n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 70_000), rng.integers(70_000, 3_000_000)]))
+        off_in, off_out = int(rng.integers(0, 8)), int(rng.integers(0, 8))
+        chained, segs = int(rng.integers(0, 2)), int(rng.choice([-1, 1, 2, 5, 64, 1000, 4096]))
+        ssam.ssam_set_tuning("scan_chained", chained)
+        ssam.ssam_set_tuning("scan_segments", segs)
+        print(f"scan case {case}: {np.dtype(dt).name} n={n} offsets {off_in}/{off_out} one pass {chained} segments<={segs}", flush=True)
+        src = dev_pool[dt][off_in:off_in + n]
+        out = torch.full((n + 16,), -3.0, dtype=src.dtype, device="cuda")
+        ssam.ssam_scan(src, out[off_out:off_out + n])
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.all(got[:off_out] == -3.0) and np.all(got[off_out + n:] == -3.0), "wrote outside the output"
+        check(got[off_out:off_out + n], pool[dt][off_in:off_in + n], f"case {case}")
+    for name in KNOBS:
+        ssam.ssam_set_tuning(name, -1)
+
+
 def test_one_pass_scans_on_two_streams_at_once(ssam):
     """Two one-pass scans in flight on their own streams with their own workspaces: the waves of one
     only ever wait for waves of the same launch that already run, so sharing the device costs time,
