@@ -157,8 +157,9 @@ int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int 
  *     the waves before it, always in the same order (1 read + 1 write per element, results
  *     reproducible run to run).  Waves take segments from a ticket counter, so they only wait
  *     for waves already running, and every wait is bounded: if a wave runs out of polls (a
- *     device shared with other work) it raises a flag, 8-byte word 16 of the workspace, and the
- *     three launches, enqueued behind the pass and gated on that flag, redo the array.
+ *     device shared with other work) it raises a flag, 8-byte word 16 of the workspace, and a
+ *     one-workgroup kernel enqueued behind the pass (it returns at once otherwise) redoes the
+ *     array, slowly (about 30 ms per GiB).
  * Totals that cross a 64-lane step are carried in fp64 for both element types, so the result is
  * within a few roundings of the element type of the exact prefix, relative to the sum of
  * magnitudes.  A non-finite partial sum makes the later results non-finite (an infinity may read

@@ -18,9 +18,9 @@
 // in registers, publishes the segment's sum, obtains the sum of everything before it from what
 // earlier waves published, and writes its outputs: n elements read, n written.  Segments are
 // handed out through a ticket counter, so a wave only ever waits for waves that are already
-// running.  Every wait is bounded: a wave that gives up raises a flag and writes nothing, and the
-// three launches above, enqueued behind the pass and gated on that flag, then redo the whole
-// array.  What is published, with fan = 64 (one item per lane of the reader):
+// running.  Every wait is bounded: a wave that gives up raises a flag and writes nothing, and a
+// one-workgroup kernel enqueued behind the pass (it returns at once unless the flag is up) then
+// redoes the whole array.  What is published, with fan = 64 (one item per lane of the reader):
 //   A[s]   sum of segment s                          by wave s, right after its loads
 //   G[g]   sum of the 64 segments of group g         by the last wave of the group, once it has
 //                                                    the A's of its group (and nothing else)
@@ -73,12 +73,10 @@ constexpr int chain_rounds(int dtype, bool aligned)
 }
 constexpr int kChainFan = 64;                                      // items summed per level = lanes
 constexpr long long kChainMaxSegments = 64LL * 64 * 64;            // three levels
-constexpr int kChainRedoSegments = 4096;                           // segments of the gated three launches
 constexpr long long kChainMinBytes = 128LL << 20;                  // shorter arrays take the three launches (as fast or faster there)
 constexpr int kChainSpinLimit = 1 << 16;                           // polls before a wave gives up
 using Word = unsigned long long;
-// Workspace of the one-pass schedule, in 8-byte words: ticket counter, flag, SP, G, A, then the
-// segment sums of the gated three launches.  The ticket counter (one atomic per workgroup) and
+// Workspace of the one-pass schedule, in 8-byte words: ticket counter, flag, SP, G, A.  The ticket counter (one atomic per workgroup) and
 // every SP item (read by all 4096 waves of the following run) have a 128-byte line to themselves:
 // sharing one line made the runs that watch it several times slower.
 constexpr long long kWsTicket = 0, kWsGaveUp = 16, kWsSP = 32, kWsSPStride = 16,
@@ -159,18 +157,11 @@ struct ScanPlan {
     int reverse;         // launch 3 takes the segments last to first
 };
 
-// The three launches run unconditionally (gate == nullptr) or only if the word at gate is not 0.
-__device__ __forceinline__ bool gate_closed(const Word* gate)
-{
-    return gate && __hip_atomic_load(gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0;
-}
-
 // Launch 1: sums[s] = sum of segment s.
 template <class T, bool ALIGNED>
-__global__ __launch_bounds__(kBlock) void scan_reduce(const T* __restrict__ a, double* __restrict__ sums, ScanPlan pl, const Word* gate)
+__global__ __launch_bounds__(kBlock) void scan_reduce(const T* __restrict__ a, double* __restrict__ sums, ScanPlan pl)
 {
     constexpr int V = ScanVec<T>::V;
-    if (gate_closed(gate)) return;
     const int lane = threadIdx.x & (kWave - 1);
     const long long s = (long long)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (s >= pl.segments) return;
@@ -200,10 +191,9 @@ __global__ __launch_bounds__(kBlock) void scan_reduce(const T* __restrict__ a, d
 
 // Launch 2: sums[s] <- sums[0] + ... + sums[s-1], in place, by one workgroup.  A thread owns up to
 // kOffsetsEach consecutive sums and fetches them all before it adds any.
-__global__ __launch_bounds__(kOffsetsThreads) void scan_offsets(double* __restrict__ sums, int segments, const Word* gate)
+__global__ __launch_bounds__(kOffsetsThreads) void scan_offsets(double* __restrict__ sums, int segments)
 {
     __shared__ double wave_total[kOffsetsThreads / kWave];
-    if (gate_closed(gate)) return;
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t >> 6;
     const int each = (segments + kOffsetsThreads - 1) / kOffsetsThreads;
     const int i0 = t * each;
@@ -227,10 +217,9 @@ __global__ __launch_bounds__(kOffsetsThreads) void scan_offsets(double* __restri
 
 // Launch 3: the scan proper.  offsets == nullptr: a single segment that starts from 0.
 template <class T, bool ALIGNED>
-__global__ __launch_bounds__(kBlock) void scan_segments(const T* a, T* b, const double* __restrict__ offsets, ScanPlan pl, const Word* gate)
+__global__ __launch_bounds__(kBlock) void scan_segments(const T* a, T* b, const double* __restrict__ offsets, ScanPlan pl)
 {
     constexpr int V = ScanVec<T>::V;
-    if (gate_closed(gate)) return;
     const int lane = threadIdx.x & (kWave - 1);
     long long s = (long long)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (s >= pl.segments) return;
@@ -386,7 +375,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
             group_out = true;
         }
         if (!__any(!(ok_mine && ok_prev && ok_grp && ok_run))) break;
-        if (polls++ >= pl.spin_limit) {      // give up: the gated launches behind this pass redo the array
+        if (polls++ >= pl.spin_limit) {      // give up: the kernel behind this pass redoes the array
             if (lane == 0) __hip_atomic_store(ws + kWsGaveUp, (Word)1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
@@ -439,6 +428,61 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
 #endif
 }
 
+// The fallback of the one-pass schedule, enqueued behind every pass: if a wave gave up, ONE
+// workgroup scans the whole array (16 waves, each a contiguous piece of kScanRounds wave-rounds per
+// step, piece sums exchanged through LDS, one barrier per step); otherwise it returns at once.
+// It is slow (about 30 ms per GiB) and only runs after a wave has already waited for 2^16 polls.
+template <class T, bool ALIGNED>
+__global__ __launch_bounds__(kOffsetsThreads) void scan_redo(const T* __restrict__ a, T* __restrict__ b, long long n,
+                                                             const Word* gave_up)
+{
+    if (__hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+    constexpr int V = ScanVec<T>::V;
+    constexpr int NWAVES = kOffsetsThreads / kWave;
+    __shared__ double piece_total[2][NWAVES];
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    const long long per_wave = (long long)kScanRounds * kWave * V, per_step = per_wave * NWAVES;
+    double carry = 0.0;
+    int buf = 0;
+    for (long long base = 0; base < n; base += per_step, buf ^= 1) {
+        T v[kScanRounds][V];
+        const long long e0 = base + w * per_wave + (long long)lane * V;
+#pragma unroll
+        for (int k = 0; k < kScanRounds; ++k) load_elems<T, ALIGNED>(a, e0 + (long long)k * kWave * V, n, v[k]);
+        double round_total = 0.0;
+#pragma unroll
+        for (int k = 0; k < kScanRounds; ++k) {
+#pragma unroll
+            for (int j = 1; j < V; ++j) v[k][j] += v[k][j - 1];
+            const T incl = wave_inclusive_scan(v[k][V - 1]);
+            const T before = shift_up(incl);
+#pragma unroll
+            for (int j = 0; j < V; ++j) v[k][j] += before;
+            const double t = (double)read_lane(incl, kWave - 1);
+            if (lane == k) round_total = t;
+        }
+        const double rounds_incl = wave_inclusive_scan(round_total);
+        const double round_start = shift_up(rounds_incl);
+        if (lane == kWave - 1) piece_total[buf][w] = rounds_incl;
+        __syncthreads();       // the other buffer is written next step, after every wave has passed this barrier
+        double start = carry, step_total = 0.0;
+        for (int u = 0; u < NWAVES; ++u) {
+            const double t = piece_total[buf][u];
+            if (u < w) start += t;
+            step_total += t;
+        }
+#pragma unroll
+        for (int k = 0; k < kScanRounds; ++k) {
+            const double c = start + read_lane(round_start, k);
+            T o[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) o[j] = (T)(c + (double)v[k][j]);
+            store_elems<T, ALIGNED>(b, e0 + (long long)k * kWave * V, n, o);
+        }
+        carry += step_total;
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------
 
 ScanPlan plan_scan(long long n, int dtype, int cap)
@@ -483,28 +527,28 @@ size_t three_launch_bytes(long long n, int dtype)
 
 size_t chained_bytes(long long segs)
 {
-    return segs ? (size_t)(kWsA + segs + kChainRedoSegments) * sizeof(Word) : 0;
+    return segs ? (size_t)(kWsA + segs) * sizeof(Word) : 0;
 }
 
 template <class T, bool ALIGNED>
-void launch_three(const void* d_in, void* d_out, double* sums, const ScanPlan& pl, const Word* gate, hipStream_t st)
+void launch_three(const void* d_in, void* d_out, double* sums, const ScanPlan& pl, hipStream_t st)
 {
     const unsigned blocks = (unsigned)((pl.segments + kWavesPerBlock - 1) / kWavesPerBlock);
     if (pl.segments > 1) {
         hipLaunchKernelGGL((scan_reduce<T, ALIGNED>), dim3(blocks), dim3(kBlock), 0, st,
-                           static_cast<const T*>(d_in), sums, pl, gate);
-        hipLaunchKernelGGL(scan_offsets, dim3(1), dim3(kOffsetsThreads), 0, st, sums, pl.segments, gate);
+                           static_cast<const T*>(d_in), sums, pl);
+        hipLaunchKernelGGL(scan_offsets, dim3(1), dim3(kOffsetsThreads), 0, st, sums, pl.segments);
     }
     hipLaunchKernelGGL((scan_segments<T, ALIGNED>), dim3(blocks), dim3(kBlock), 0, st,
                        static_cast<const T*>(d_in), static_cast<T*>(d_out),
-                       pl.segments > 1 ? sums : nullptr, pl, gate);
+                       pl.segments > 1 ? sums : nullptr, pl);
 }
 
 template <class T, bool ALIGNED>
 int launch_scan(const void* d_in, void* d_out, void* d_work, long long n, int dtype, long long chain_segs, hipStream_t st)
 {
     if (!chain_segs) {
-        launch_three<T, ALIGNED>(d_in, d_out, static_cast<double*>(d_work), plan_scan(n, dtype, segment_cap()), nullptr, st);
+        launch_three<T, ALIGNED>(d_in, d_out, static_cast<double*>(d_work), plan_scan(n, dtype, segment_cap()), st);
         return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
     }
     Word* ws = static_cast<Word*>(d_work);
@@ -519,8 +563,8 @@ int launch_scan(const void* d_in, void* d_out, void* d_work, long long n, int dt
     const unsigned blocks = (unsigned)((chain_segs + kWavesPerBlock - 1) / kWavesPerBlock);
     hipLaunchKernelGGL((scan_chained<T, ALIGNED>), dim3(blocks), dim3(kBlock), 0, st,
                        static_cast<const T*>(d_in), static_cast<T*>(d_out), ws, cp);
-    launch_three<T, ALIGNED>(d_in, d_out, reinterpret_cast<double*>(ws + words), plan_scan(n, dtype, kChainRedoSegments),
-                             ws + kWsGaveUp, st);
+    hipLaunchKernelGGL((scan_redo<T, ALIGNED>), dim3(1), dim3(kOffsetsThreads), 0, st,
+                       static_cast<const T*>(d_in), static_cast<T*>(d_out), n, ws + kWsGaveUp);
     return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
 }
 

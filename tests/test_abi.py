@@ -89,9 +89,9 @@ def test_scan_plan_and_validation(L):
     assert ws(1024, 0) == 0 and ws(512, 1) == 0                 # one segment: no workspace
     assert ws(1025, 0) == 16 and ws(513, 1) == 16               # two segments
     # arrays of 128 MiB and more, up to 64^3 register-resident segments of 16 KiB: the one-pass schedule
-    # (ticket and flag, 64 padded + 4096 + one per segment published sums of 8 bytes, 4096 sums for the
-    # gated launches); the three launches use at most 4096 segments
-    one_pass = lambda segs: 8 * (32 + 16 * 64 + 4096 + segs + 4096)
+    # (ticket and flag, 64 padded + 4096 + one per segment published sums of 8 bytes); the three
+    # launches use at most 4096 segments
+    one_pass = lambda segs: 8 * (32 + 16 * 64 + 4096 + segs)
     assert ws((1 << 25) - 1, 0) == 8 * 4096 and ws(1 << 25, 0) == one_pass(1 << 13)
     assert ws(1 << 28, 0) == one_pass(1 << 16) and ws(1 << 28, 1) == one_pass(1 << 17)
     assert ws(1 << 30, 0) == one_pass(1 << 18) and 8 * 4000 < ws((1 << 30) + 1, 0) <= 8 * 4096

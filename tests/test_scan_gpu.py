@@ -105,7 +105,7 @@ def test_scan_segment_overrides_unaligned_and_in_place(ssam, dtype):
 
 def gave_up(work) -> int:
     """Word 16 of the workspace of a one-pass call: nonzero if a wave ran out of polls and the
-    gated launches redid the array."""
+    fallback kernel redid the array."""
     torch.cuda.synchronize()
     return int(work.view(torch.int64)[16])
 
@@ -148,7 +148,7 @@ def test_one_pass_scan_matches_oracle(ssam, dtype):
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_one_pass_scan_that_gives_up_is_redone(ssam, dtype):
     """A poll limit of 0 set from the host makes every wave that would have to wait give up at
-    once (no wave spins); the launches gated on the flag then produce the result."""
+    once (no wave spins); the one-workgroup kernel behind the pass then produces the result."""
     per = (32 * 64 * 4) if dtype == np.float32 else (26 * 64 * 2)
     n = 300 * per + 5
     a = wl.uniform_field((n,), -1.0, 1.0, 980, dtype)
