@@ -174,9 +174,10 @@ int ssam_scan(const void *d_in, void *d_out, long long n, int dtype,
 size_t ssam_scan_workspace_bytes(long long n, int dtype);
 
 /* Measurement aid: copies nbytes (a multiple of 16; both pointers 16-byte aligned, not
- * overlapping) from d_in to d_out with a plain 16-bytes-per-lane kernel on hip_stream.  It is
- * the bandwidth ceiling for a one-read-one-write kernel and the known-size reference that
- * hardware traffic counters are scaled by. */
+ * overlapping) from d_in to d_out with a plain grid-stride 16-bytes-per-lane kernel on hip_stream.
+ * It is a reference rate for one-read-one-write kernels (not a ceiling: kernels whose waves move
+ * long contiguous runs with streaming accesses, like the one-pass scan, exceed it) and the
+ * known-size reference that hardware traffic counters are scaled by. */
 int ssam_probe_copy(const void *d_in, void *d_out, size_t nbytes, void *hip_stream);
 
 /* Measurement aid: cycles per operation of the primitives the kernels are built from -- the

@@ -179,8 +179,9 @@ hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, 
 }
 
 // ---- plain copy (measurement aid) ---------------------------------------------------------
-// 16 bytes per lane, grid-stride: the bandwidth ceiling a 1-read-1-write kernel can reach, and
-// the known-size reference the hardware traffic counters are scaled by.
+// 16 bytes per lane, grid-stride: a reference rate for 1-read-1-write kernels (tile-shaped
+// access with streaming stores exceeds it), and the known-size reference the hardware traffic
+// counters are scaled by.
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
