@@ -120,7 +120,8 @@ const char *ssam_status_string(int status);
  * "scan_order" (0 = its last launch takes the segments first to last), "scan_chained" (0 = never
  * the one-pass schedule, 1 = for every out-of-place array it can hold; built-in: from 128 MiB),
  * "scan_spin_limit" (polls a waiting wave of the one-pass schedule makes before it gives up, at
- * most 2^20; 0 makes every wave that would wait give up at once -- a test of the redo path);
+ * most 2^20; 0 makes every wave that would wait give up at once -- a test of the redo path),
+ * "scan_one_group" (largest element count scanned by one workgroup in one launch; 0 = never);
  * ssam_scan_workspace_bytes follows these.
  * value < 0 restores the built-in choice.  Returns SSAM_OK or SSAM_ERR_ENUM for an unknown name. */
 int ssam_set_tuning(const char *name, int value);
@@ -148,8 +149,9 @@ int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int 
  * the call's work on hip_stream has finished (two calls in flight must not share one); it may be
  * NULL when that size is 0 (short arrays).  The call enqueues its launches on hip_stream and
  * returns without waiting and without allocating; no memset is enqueued, so it can be captured.
- * Two schedules, chosen by size:
- *   - three launches (below 128 MiB, and always in place): the array is cut into contiguous
+ * Schedules, chosen by size:
+ *   - one workgroup, one launch (up to 128 KiB; no workspace);
+ *   - three launches (below 128 MiB, and always in place beyond 128 KiB): the array is cut into contiguous
  *     segments, one per wave; segment sums, their exclusive prefixes, the scan of every segment
  *     (2 reads + 1 write per element);
  *   - one pass (from 128 MiB, out of place, up to 2^30 fp32 / 2^29 fp64 elements): every wave

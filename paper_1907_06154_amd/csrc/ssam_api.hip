@@ -572,6 +572,7 @@ int ssam_set_tuning(const char* name, int value)
     else if (!strcmp(name, "scan_order")) g_scan_order = value;
     else if (!strcmp(name, "scan_chained")) g_scan_chained = value;
     else if (!strcmp(name, "scan_spin_limit")) g_scan_spin_limit = value;
+    else if (!strcmp(name, "scan_one_group")) g_scan_one_group = value;
     else return SSAM_ERR_ENUM;
     return SSAM_OK;
 }

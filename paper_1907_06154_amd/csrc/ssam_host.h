@@ -15,9 +15,10 @@
 namespace ssam {
 
 // Launch parameters a caller may override through ssam_set_tuning (negative = built-in).
-// Scan overrides (ssam_set_tuning "scan_segments", "scan_order", "scan_chained", "scan_spin_limit");
+// Scan overrides (ssam_set_tuning "scan_segments", "scan_order", "scan_chained", "scan_spin_limit",
+// "scan_one_group");
 // defined beside the scan kernels.
-extern std::atomic<int> g_scan_segments, g_scan_order, g_scan_chained, g_scan_spin_limit;
+extern std::atomic<int> g_scan_segments, g_scan_order, g_scan_chained, g_scan_spin_limit, g_scan_one_group;
 
 struct Tuning {
     int rows_per_wave = -1;    // 2D: output rows one wave marches over

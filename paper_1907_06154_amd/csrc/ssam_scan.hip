@@ -49,12 +49,13 @@
 
 namespace ssam {
 
-std::atomic<int> g_scan_segments{-1}, g_scan_order{-1}, g_scan_chained{-1}, g_scan_spin_limit{-1};
+std::atomic<int> g_scan_segments{-1}, g_scan_order{-1}, g_scan_chained{-1}, g_scan_spin_limit{-1}, g_scan_one_group{-1};
 
 namespace {
 
 constexpr int kScanMaxSegments = 4096;   // upper limit of waves per launch = doubles in the workspace
 constexpr int kScanRounds = 4;           // wave-rounds in flight per wave (loads issued together)
+constexpr long long kOneGroupBytes = 128 << 10;  // arrays up to this size: one workgroup, one launch (8 instead of 12.5 us)
 constexpr int kOffsetsThreads = 1024;    // the one workgroup of launch 2 ...
 constexpr int kOffsetsEach = kScanMaxSegments / kOffsetsThreads;   // ... and the sums one of its threads owns
 
@@ -428,15 +429,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
 #endif
 }
 
-// The fallback of the one-pass schedule, enqueued behind every pass: if a wave gave up, ONE
-// workgroup scans the whole array (16 waves, each a contiguous piece of kScanRounds wave-rounds per
-// step, piece sums exchanged through LDS, one barrier per step); otherwise it returns at once.
-// It is slow (about 30 ms per GiB) and only runs after a wave has already waited for 2^16 polls.
+// The whole scan by ONE workgroup: 16 waves, each a contiguous piece of kScanRounds wave-rounds per
+// step, piece sums exchanged through LDS, one barrier per step; in place is fine.  Two uses:
+//  - short arrays (gave_up == nullptr): one launch instead of three, which is all that counts there;
+//  - the fallback of the one-pass schedule, enqueued behind every pass: it returns at once unless
+//    the word at gave_up is set.  It is slow (about 30 ms per GiB) and only runs after a wave has
+//    already waited for 2^16 polls.
 template <class T, bool ALIGNED>
-__global__ __launch_bounds__(kOffsetsThreads) void scan_redo(const T* __restrict__ a, T* __restrict__ b, long long n,
-                                                             const Word* gave_up)
+__global__ __launch_bounds__(kOffsetsThreads) void scan_one_group(const T* a, T* b, long long n, const Word* gave_up)
 {
-    if (__hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+    if (gave_up && __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
     constexpr int V = ScanVec<T>::V;
     constexpr int NWAVES = kOffsetsThreads / kWave;
     __shared__ double piece_total[2][NWAVES];
@@ -519,8 +521,16 @@ long long chained_segments(long long n, int dtype, int rounds)
     return (n + per - 1) / per;
 }
 
+// Arrays up to this many elements are scanned by one workgroup in one launch (no workspace).
+long long one_group_limit(int dtype)
+{
+    const int v = g_scan_one_group.load();
+    return v < 0 ? kOneGroupBytes / (dtype == SSAM_F32 ? 4 : 8) : v;
+}
+
 size_t three_launch_bytes(long long n, int dtype)
 {
+    if (n <= one_group_limit(dtype)) return 0;
     const ScanPlan pl = plan_scan(n, dtype, segment_cap());
     return pl.segments > 1 ? (size_t)pl.segments * sizeof(double) : 0;
 }
@@ -547,6 +557,11 @@ void launch_three(const void* d_in, void* d_out, double* sums, const ScanPlan& p
 template <class T, bool ALIGNED>
 int launch_scan(const void* d_in, void* d_out, void* d_work, long long n, int dtype, long long chain_segs, hipStream_t st)
 {
+    if (!chain_segs && n <= one_group_limit(dtype)) {
+        hipLaunchKernelGGL((scan_one_group<T, ALIGNED>), dim3(1), dim3(kOffsetsThreads), 0, st,
+                           static_cast<const T*>(d_in), static_cast<T*>(d_out), n, static_cast<const Word*>(nullptr));
+        return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    }
     if (!chain_segs) {
         launch_three<T, ALIGNED>(d_in, d_out, static_cast<double*>(d_work), plan_scan(n, dtype, segment_cap()), st);
         return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
@@ -563,7 +578,7 @@ int launch_scan(const void* d_in, void* d_out, void* d_work, long long n, int dt
     const unsigned blocks = (unsigned)((chain_segs + kWavesPerBlock - 1) / kWavesPerBlock);
     hipLaunchKernelGGL((scan_chained<T, ALIGNED>), dim3(blocks), dim3(kBlock), 0, st,
                        static_cast<const T*>(d_in), static_cast<T*>(d_out), ws, cp);
-    hipLaunchKernelGGL((scan_redo<T, ALIGNED>), dim3(1), dim3(kOffsetsThreads), 0, st,
+    hipLaunchKernelGGL((scan_one_group<T, ALIGNED>), dim3(1), dim3(kOffsetsThreads), 0, st,
                        static_cast<const T*>(d_in), static_cast<T*>(d_out), n, ws + kWsGaveUp);
     return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
 }

@@ -86,8 +86,12 @@ def test_scan_plan_and_validation(L):
     vp = ctypes.c_void_p
     ws = L.ssam_scan_workspace_bytes
     assert ws(0, 0) == 0 and ws(-5, 0) == 0 and ws(1000, 9) == 0
+    assert ws(32768, 0) == 0 and ws(16384, 1) == 0              # up to 128 KiB: one workgroup, no workspace
+    assert ws(32769, 0) == 8 * 33 and ws(16385, 1) == 8 * 33    # beyond: segments of 4 wave-rounds
+    assert L.ssam_set_tuning(b"scan_one_group", 0) == 0
     assert ws(1024, 0) == 0 and ws(512, 1) == 0                 # one segment: no workspace
     assert ws(1025, 0) == 16 and ws(513, 1) == 16               # two segments
+    assert L.ssam_set_tuning(b"scan_one_group", -1) == 0
     # arrays of 128 MiB and more, up to 64^3 register-resident segments of 16 KiB: the one-pass schedule
     # (ticket and flag, 64 padded + 4096 + one per segment published sums of 8 bytes); the three
     # launches use at most 4096 segments

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-KNOBS = ("scan_segments", "scan_order", "scan_chained", "scan_spin_limit")
+KNOBS = ("scan_segments", "scan_order", "scan_chained", "scan_spin_limit", "scan_one_group")
 TOL = {np.dtype(np.float32): 2e-6, np.dtype(np.float64): 1e-13}
 
 
@@ -41,8 +41,11 @@ SIZES = [1, 2, 3, 63, 64, 65, 127, 128, 255, 256, 257, 511, 1023, 1024, 1025, 20
          65536, 100003, (1 << 20) + 17, (1 << 23) + 5]
 
 
+@pytest.mark.parametrize("one_group", [-1, 0, 1 << 22])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
-def test_scan_matches_oracle(ssam, dtype):
+def test_scan_matches_oracle(ssam, dtype, one_group):
+    """one_group: the built-in limit of the one-workgroup launch (128 KiB), never, or up to 4 Mi elements."""
+    ssam.ssam_set_tuning("scan_one_group", one_group)
     for k, n in enumerate(SIZES):
         lo = -1.0 if k % 2 == 0 else 0.0
         a = wl.uniform_field((n,), lo, 1.0, 900 + k, dtype)
@@ -50,6 +53,12 @@ def test_scan_matches_oracle(ssam, dtype):
         got = ssam.ssam_scan(torch.from_numpy(a).cuda())
         torch.cuda.synchronize()
         check(got.cpu().numpy(), a, f"n={n}")
+        if n <= 70000:                       # in place
+            x = torch.from_numpy(a).cuda()
+            ssam.ssam_scan(x, x)
+            torch.cuda.synchronize()
+            check(x.cpu().numpy(), a, f"in place n={n}")
+    ssam.ssam_set_tuning("scan_one_group", -1)
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
