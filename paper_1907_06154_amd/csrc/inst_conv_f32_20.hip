@@ -1,4 +1,7 @@
 // Compiled register-cache instances: inst_conv_f32_20.hip
 #include "ssam_kernel2d.h"
 
-SSAM_INSTANCE_2D(float, SSAM_F32, 4, 4, 20, 20, 10, 2);
+// Default: products on the matrix cores (faster from 7x7 on); variant 5: on the vector unit.
+
+SSAM_INSTANCE_2D_MFMA(4, 20, 20, 10, 2, 1, 2, 0);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 4, 20, 20, 10, 2, 1, 2, 5);

@@ -1,8 +1,12 @@
 // Compiled instances: square filters of the 2x2 .. 20x20 sweep (Sec. 6.2), small sizes.
 #include "ssam_kernel2d.h"
 
+// Default: products on the matrix cores (faster from 7x7 on); variant 5: on the vector unit.
+
 SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 2, 2, 1, 2, 1, 2, 0);
 SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 4, 4, 2, 2, 1, 2, 0);
 SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 6, 6, 3, 2, 1, 2, 0);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 7, 7, 3, 2, 1, 2, 0);
-SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 8, 8, 4, 2, 0, 2, 0);
+SSAM_INSTANCE_2D_MFMA(4, 7, 7, 3, 2, 1, 2, 0);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 7, 7, 3, 2, 1, 2, 5);
+SSAM_INSTANCE_2D_MFMA(4, 8, 8, 4, 2, 1, 2, 0);
+SSAM_INSTANCE_2D_V(float, SSAM_F32, 4, 8, 8, 8, 4, 2, 0, 2, 5);

@@ -405,6 +405,155 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
         for (int j = 0; j < V; ++j) out[p][j] = have[j] ? sum[p][j] : T(0);
 }
 
+// ---- the same evaluation on the matrix cores -------------------------------------------
+// v_mfma_f32_4x4x1 (16 blocks of 4 lanes, K = 1) computes, in lane l and for i = 0..3,
+//     d[i] = a(lane 4*(l/4) + i) * b(lane l) + c[i]
+// i.e. every lane multiplies ITS OWN b by the four a values of its group of four lanes.  With
+// b = the lane's cached row k of one of its columns, a = the filter-column value that row k
+// contributes to window position i with (w[k - i][m], the same pattern in every group of four),
+// and c/d = the four window sums of one output column, one instruction performs the four
+// multiply-adds that row k owes to the P = 4 window positions -- the products of Sec. 4.3 at twice
+// the rate of the vector unit (32 instead of 16 multiply-adds per SIMD and cycle, full fp32), while the
+// vector unit is left with the lane shifts.  N + 3 instructions replace 4 N fused multiply-adds
+// per filter column and output column; rows k that meet no tap of the column are skipped.
+//
+// The a operands come from a table in LDS, laid out for this: tab[(m * (N + 3) + k) * 4 + q] =
+// w[k - q][m], 0 outside the filter; each lane reads entry q = lane % 4 (four addresses per read,
+// broadcast, no conflict).  The caller fills the table once per workgroup (fill_mfma_weights).
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <class Mask>
+struct MfmaWeights {
+    static constexpr int kRows = Mask::kN + 3;              // rows of the window of four positions
+    static constexpr int kWords = Mask::kM * kRows * 4;
+};
+
+// Workgroup-cooperative; the caller synchronises afterwards.
+template <class Mask>
+__device__ __forceinline__ void fill_mfma_weights(ConstPtr<float> w, float* tab)
+{
+    constexpr int N = Mask::kN, C = MfmaWeights<Mask>::kRows;
+    for (int e = threadIdx.x; e < MfmaWeights<Mask>::kWords; e += blockDim.x) {
+        const int q = e & 3, k = (e >> 2) % C, m = (e >> 2) / C;
+        const int n = k - q;
+        tab[e] = (n >= 0 && n < N && Mask::tap(n, m)) ? w[Mask::widx(n, m)] : 0.0f;
+    }
+}
+
+template <class Mask>
+__host__ __device__ constexpr bool window_row_meets_column(int k, int m)
+{
+    for (int q = 0; q < 4; ++q)
+        if (k - q >= 0 && k - q < Mask::kN && Mask::tap(k - q, m)) return true;
+    return false;
+}
+
+// column_products on the matrix cores: tab_lane = table + lane % 4; s[j] holds the four window
+// sums of output column j.
+template <int V, class Mask, int DX, int COL, class Rows>
+__device__ __forceinline__ void column_products_mfma(const Rows& r, const float* tab_lane, v4f (&s)[V], bool (&set)[V])
+{
+    constexpr int C = MfmaWeights<Mask>::kRows, m = Mask::kAX + DX;
+    // the opaque zero pins the table reads of this filter column to this place: otherwise the
+    // compiler requests the whole table ahead and spills the registers it needs for that
+    const float* col = tab_lane + m * C * 4 + opaque_zero();
+    float a[C];      // the column's operands are requested together, so that one wait covers them all
+#pragma unroll
+    for (int k = 0; k < C; ++k)
+        if (window_row_meets_column<Mask>(k, m)) a[k] = col[k * 4];
+    __builtin_amdgcn_sched_barrier(0);   // or the scheduler moves every read next to its use and waits for each
+#pragma unroll
+    for (int k = 0; k < C; ++k) {
+        if (window_row_meets_column<Mask>(k, m)) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const int i = j + COL;
+                if (i >= 0 && i < V) {
+                    const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                    s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[k], r.at(k, i), c, 0, 0, 0);
+                    set[j] = true;
+                }
+            }
+        }
+    }
+}
+
+// systolic_rows for fp32, P = 4, no incoming sums, with the products on the matrix cores: the same
+// two converging chains and the same shifts.
+template <int V, class Mask, class Rows>
+__device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* tab_lane, float (&out)[4][V])
+{
+    static_assert(Rows::kRows >= Mask::kN + 3, "register cache too small for the sliding window");
+    constexpr int DL = (Mask::kLeft + V - 1) / V;
+    constexpr int DR = (Mask::kRight + V - 1) / V;
+    v4f sum[V];
+    bool have[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) have[j] = false;
+
+    if constexpr (DL > 0) {
+        v4f s[V];
+        bool got[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) got[j] = false;
+        static_for<DL>([&](auto dc) __attribute__((always_inline)) {
+            constexpr int d = DL - decltype(dc)::value;
+            static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+                constexpr int dx = decltype(cc)::value - (V - 1) - d * V;
+                if constexpr (dx >= -Mask::kLeft && dx <= -1)
+                    column_products_mfma<V, Mask, dx, dx + d * V, Rows>(r, tab_lane, s, got);
+            });
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                if (got[j]) {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) s[j][p] = shift_up(s[j][p]);
+                }
+        });
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+            if (got[j]) {
+                sum[j] = have[j] ? sum[j] + s[j] : s[j];
+                have[j] = true;
+            }
+    }
+    if constexpr (DR > 0) {
+        v4f s[V];
+        bool got[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) got[j] = false;
+        static_for<DR>([&](auto dc) __attribute__((always_inline)) {
+            constexpr int d = DR - decltype(dc)::value;
+            static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+                constexpr int dx = decltype(cc)::value - (V - 1) + d * V;
+                if constexpr (dx >= 1 && dx <= Mask::kRight)
+                    column_products_mfma<V, Mask, dx, dx - d * V, Rows>(r, tab_lane, s, got);
+            });
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                if (got[j]) {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) s[j][p] = shift_down(s[j][p]);
+                }
+        });
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+            if (got[j]) {
+                sum[j] = have[j] ? sum[j] + s[j] : s[j];
+                have[j] = true;
+            }
+    }
+    static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
+        constexpr int dx = decltype(cc)::value - (V - 1);
+        if constexpr (dx >= -Mask::kLeft && dx <= Mask::kRight)
+            column_products_mfma<V, Mask, dx, dx, Rows>(r, tab_lane, sum, have);
+    });
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int j = 0; j < V; ++j) out[p][j] = have[j] ? sum[j][p] : 0.0f;
+}
+
 // Map the hardware block id to a logical one so that consecutive logical blocks (which
 // share halo rows and cache lines) run on the same XCD and hence behind the same L2:
 // hardware deals block b to XCD b % 8.  nblocks_padded is a multiple of 8.

@@ -30,12 +30,23 @@ struct Args2D {
     T w[NW];            // packed per Mask::widx, read through scalar loads (wave-uniform broadcast, Sec. 4.6)
 };
 
-template <typename T, int V, int P, class Mask, bool PREFETCH, int NT>
+// ENGINE 0: products on the vector unit (any type, any P).  ENGINE 1: products on the matrix cores
+// (fp32, P = 4; see systolic_rows_mfma), with the filter laid out for them in LDS.
+template <typename T, int V, int P, class Mask, bool PREFETCH, int NT, int ENGINE = 0>
 __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kNW> a)
 {
     constexpr int N = Mask::kN;
     constexpr int HL = (Mask::kLeft + V - 1) / V;
     constexpr int HR = (Mask::kRight + V - 1) / V;
+    static_assert(ENGINE == 0 || (sizeof(T) == 4 && P == 4), "the matrix-core engine is fp32, four window positions");
+
+    typedef Args2D<T, Mask::kNW> Args;
+    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
+    __shared__ float mfma_tab[ENGINE == 1 ? MfmaWeights<Mask>::kWords : 1];
+    if constexpr (ENGINE == 1) {
+        fill_mfma_weights<Mask>(wts, mfma_tab);      // before any wave leaves: every thread helps and waits
+        __syncthreads();
+    }
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -58,8 +69,6 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
     const int xl = xw0 + min(lane, used_lanes - 1) * V;   // first column this lane loads
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
-    typedef Args2D<T, Mask::kNW> Args;
-    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
     const bool lane_stores = lane >= HL && lane < HL + a.valid_lanes && xc < W;
     // per-lane column masks for the general path (a lane's V columns are all inside or all outside
     // the grid when rows are V-aligned)
@@ -163,7 +172,10 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
                     }
 
                     T acc[P][V];
-                    systolic_rows<T, V, P, Mask, false>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, wts, acc, acc);
+                    if constexpr (ENGINE == 1)
+                        systolic_rows_mfma<V, Mask>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, mfma_tab + (lane & 3), acc);
+                    else
+                        systolic_rows<T, V, P, Mask, false>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, wts, acc, acc);
                     store_rows(y, acc);
 
                     // rows P .. P+KEEP-1 of this window open the next one
@@ -184,7 +196,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
     else march(std::integral_constant<int, 2>{});
 }
 
-template <typename T, int V, int P, class Mask, bool PREFETCH, int NT>
+template <typename T, int V, int P, class Mask, bool PREFETCH, int NT, int ENGINE = 0>
 hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     constexpr int M = Mask::kM, N = Mask::kN;
@@ -203,7 +215,7 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
         // arithmetic-heavy filters: every wave takes about the same time, so the tile count should
         // fill the machine's wave slots a whole number of times (a partly filled last round costs
         // a full one).  Measured on 8192^2, 20x20: 57 -> 73 GStencil/s.
-        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_kernel<T, V, P, Mask, PREFETCH, NT>));
+        static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_kernel<T, V, P, Mask, PREFETCH, NT, ENGINE>));
         rows = balanced_rows(pr.H, P, g.strips_x, slots, 3 * (N - 1));
     } else {
         // bandwidth-bound: the shortest tiles measured best -- one or two groups per wave, about twice the
@@ -238,7 +250,7 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     for (int n = 0; n < N; ++n)
         for (int m = 0; m < M; ++m)
             if (Mask::tap(n, m)) a.w[Mask::widx(n, m)] = w[n * M + m];
-    hipLaunchKernelGGL((ssam2d_kernel<T, V, P, Mask, PREFETCH, NT>), dim3(g.blocks), dim3(kBlock), 0, pr.stream, a);
+    hipLaunchKernelGGL((ssam2d_kernel<T, V, P, Mask, PREFETCH, NT, ENGINE>), dim3(g.blocks), dim3(kBlock), 0, pr.stream, a);
     return hipGetLastError();
 }
 
@@ -251,5 +263,11 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
         VARIANT,                                                                                      \
         &::ssam::launch2d<T, V, P, ::ssam::TapMask<M, N, AX, (N) / 2, BUDGET>, (PREFETCH) != 0, NT>})
 #define SSAM_INSTANCE_2D(T, DT, V, P, M, N, AX, BUDGET) SSAM_INSTANCE_2D_V(T, DT, V, P, M, N, AX, BUDGET, 1, 2, 0)
+// The same with the products on the matrix cores (fp32, P = 4); the name ends in "mx".
+#define SSAM_INSTANCE_2D_MFMA(V, M, N, AX, BUDGET, PREFETCH, NT, VARIANT)                                 \
+    static ::ssam::Register2D SSAM_CAT(reg2d_, __COUNTER__)(::ssam::Instance2D{                      \
+        "float_M" #M "N" #N "_b" #BUDGET "_v" #V "p4f" #PREFETCH "nt" #NT "mx", SSAM_F32, M, N, AX, BUDGET, \
+        VARIANT,                                                                                      \
+        &::ssam::launch2d<float, V, 4, ::ssam::TapMask<M, N, AX, (N) / 2, BUDGET>, (PREFETCH) != 0, NT, 1>})
 
 }  // namespace ssam

@@ -159,7 +159,7 @@ def test_shape_classification(L):
         assert name.startswith(prefix), (nm, name)
     # a shape without a compiled instance runs inside the smallest compiled square box that holds it ...
     name, g = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((4, 7), dtype=np.float32), "zero"))
-    assert name == "float_M7N7_b2_v4p8f1nt2+embedded" and g["halo_lanes"] == 2
+    assert name == "float_M7N7_b2_v4p4f1nt2mx+embedded" and g["halo_lanes"] == 2   # the matrix-core instance is the 7x7 default
     name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones((1, 6), dtype=np.float32), "zero"))
     assert name.startswith("float_M6N6_b2") and name.endswith("+embedded")
     # ... one-dimensional filters of odd length have instances of their own ...
