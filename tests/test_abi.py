@@ -127,6 +127,25 @@ def parse(desc):
     return name, out
 
 
+def test_dense_fp32_filters_from_7x7_on_use_the_matrix_cores(L):
+    """The default instance of a dense fp32 square filter evaluates its column products on the matrix
+    cores ("...mx") from 7x7 on; variant 5 is the vector-unit instance of the same shape; smaller
+    filters and fp64 have the vector-unit kernels only."""
+    for m in range(2, 21):
+        f = wl.seeded_filter(m, m, 1, np.float32)
+        name, g = parse(ssam.ssam_describe("conv2d", (2048, 2048), f, "clamp"))
+        assert name.startswith("float_M%dN%d_b2" % (m, m)) and name.endswith("mx") == (m >= 7), name
+        if m >= 7:
+            assert g["P"] == 4 and g["V"] == 4
+            ssam.ssam_set_tuning("variant", 5)
+            other, _ = parse(ssam.ssam_describe("conv2d", (2048, 2048), f, "clamp"))
+            ssam.ssam_set_tuning("variant", -1)
+            assert other.startswith("float_M%dN%d_b2" % (m, m)) and not other.endswith("mx"), other
+    c = wl.seeded_coefficients(wl.mask_box(4, 4), 3, np.float64)[0]
+    name, _ = parse(ssam.ssam_describe("stencil2d", (2048, 2048), c, "zero"))
+    assert name.startswith("double_M9N9_b2") and not name.endswith("mx")
+
+
 def test_overlapped_blocking_geometry(L):
     """Tile plan re-derived from Sec. 4.5 / 4.7 for 64 lanes of V columns: a wave caches 64*V
     columns, stores valid_lanes*V of them (valid_lanes <= 64 - halo lanes), and the strips cover W."""

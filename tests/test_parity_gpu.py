@@ -51,6 +51,25 @@ def test_conv2d_f32(ssam, MN, boundary):
         assert_parity(got, want, filt, 1.0, f"conv {M}x{N} {boundary} {H}x{W}")
 
 
+@pytest.mark.parametrize("m", [7, 8, 9, 12, 14, 15, 17, 20])
+def test_matrix_core_and_vector_unit_instances_agree_with_the_oracle(ssam, m):
+    """Dense fp32 filters from 7x7 on run on the matrix cores by default and on the vector unit as
+    variant 5: both against the oracle, on grids with ragged strips and short tiles."""
+    filt = wl.seeded_filter(m, m, 700 + m, np.float32)
+    for k, (H, W) in enumerate([(131, 517), (64, 1024), (9, 260)]):
+        img = wl.uniform_field((H, W), -1.0, 1.0, 720 + k, np.float32)
+        for boundary in ("clamp", "zero"):
+            want = oracle.conv2d(img, filt, boundary)
+            for variant in (-1, 5):
+                ssam.ssam_set_tuning("variant", variant)
+                name = ssam.ssam_describe("conv2d", (H, W), filt, boundary).split()[0]
+                assert name.endswith("mx") == (variant == -1), name
+                print(f"conv {m}x{m} {boundary} {H}x{W} {name}", flush=True)
+                got = host(ssam.ssam_conv2d(dev(img), filt, boundary))
+                assert_parity(got, want, filt, 1.0, f"{name} {boundary} {H}x{W}")
+    ssam.ssam_set_tuning("variant", -1)
+
+
 @pytest.mark.parametrize("MN", [(5, 7), (7, 5), (1, 4), (4, 1), (1, 15), (15, 1), (1, 20), (20, 1), (2, 16), (7, 13), (13, 1)])
 def test_odd_filter_shapes_and_anchors_f32(ssam, MN):
     """Filters without an instance of their own shape -- non-square, one-dimensional, anchored off the
