@@ -37,13 +37,13 @@ ALU_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}   # published vector peaks (fp32 f
 # kernels of the iterative 2D cases, by case and kernel instance; offline figures, not re-measured
 # by this script.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_conv3x3_f32": 537637944,
-    "c2_conv5x5_f32": 538180108,
-    "c2_conv9x9_f32": 571005150,
-    "c2_conv15x15_f32": 574703058,
-    "c2_conv20x20_f32": 586893240,
-    "c2_conv3x11_f32": 576181913,
-    "c2_conv11x3_f32": 552304557,
+    "c2_conv3x3_f32": 537671369,
+    "c2_conv5x5_f32": 538194718,
+    "c2_conv9x9_f32": 570754529,
+    "c2_conv15x15_f32": 574873014,
+    "c2_conv20x20_f32": 586910020,
+    "c2_conv3x11_f32": 575620141,
+    "c2_conv11x3_f32": 552730765,
     "c3_2d_box_r1_f64": 1075826419,
     "c3_2d_box_r2_f64": 1076305303,
     "c3_2d_star_r4_f64": 1078286643,
