@@ -309,9 +309,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     const long long s = (long long)ticket * kWavesPerBlock + (threadIdx.x >> 6);   // every lower-numbered segment has a running wave
     if (s >= pl.segments) return;
 
-#if defined(SSAM_SCAN_STATS)
-    const long long c_start = wall_clock64();
-#endif
     T v[kChainRounds][V];
     const long long e0 = (s * kChainRounds * kWave + lane) * V;
 #pragma unroll
@@ -331,9 +328,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     Word* const G = ws + kWsG;
     Word* const SP = ws + kWsSP;
     if (lane == 0) publish(A + s, own);
-#if defined(SSAM_SCAN_STATS)
-    const long long c_loaded = wall_clock64();
-#endif
 
     // The scan inside the segment, while the sums of the earlier waves arrive: afterwards v holds
     // every element's prefix within its wave-round, and lane k the sum of the rounds before round k.
@@ -402,9 +396,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     const double before_group = (read_lane(need_run ? item_value(w_run) : 0.0, 0) + sum_grp) + prev_group;
     if (i == kChainFan - 1 && gi == kChainFan - 1 && lane == 0)
         publish(SP + kWsSPStride * q, marked(before_group + group_sum(sum_mine, own)));
-#if defined(SSAM_SCAN_STATS)
-    const long long c_waited = wall_clock64();
-#endif
 
     // only the start value is missing now: add it, round once, store
     const double start = before_group + sum_mine;
@@ -416,17 +407,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         for (int j = 0; j < V; ++j) o[j] = (T)(c + (double)v[k][j]);
         store_elems<T, ALIGNED, true>(b, e0 + (long long)k * kWave * V, pl.n, o);
     }
-#if defined(SSAM_SCAN_STATS)
-    // Diagnostic build only (the workspace must then be at least 16 MiB): per segment, the
-    // constant-rate clock at start, after the loads, after the waits, at the end, and the polls,
-    // 8 words from word 2^18 on.
-    if (lane == 0) {
-        Word* rec = ws + (1 << 18) + 8 * s;
-        rec[0] = (Word)c_start; rec[1] = (Word)c_loaded; rec[2] = (Word)c_loaded; rec[3] = (Word)c_waited;
-        rec[4] = (Word)wall_clock64(); rec[5] = 0; rec[6] = (Word)polls;
-        rec[7] = (Word)(blockIdx.x);
-    }
-#endif
 }
 
 // The whole scan by ONE workgroup: 16 waves, each a contiguous piece of kScanRounds wave-rounds per
