@@ -111,7 +111,8 @@ const char *ssam_status_string(int status);
 /* Tuning override for experiments and benchmarks (not needed for correct use): sets a named
  * integer launch parameter for subsequent calls, process-wide.  Names: "rows_per_wave",
  * "valid_lanes", "planes_per_wave", "xcd_remap", "force_generic", "variant" (an alternative
- * compiled instance of the same shape, where one exists), "march_axis" (3D: 0 = march along z,
+ * compiled instance of the same shape, where one exists; e.g. 5 = the vector-unit instance of a dense
+ * fp32 filter whose default instance evaluates its products on the matrix cores), "march_axis" (3D: 0 = march along z,
  * 1 = march along y), "fuse_sweeps" (ssam_stencil_iterate: 0 or 1 = always one sweep per launch, n >= 2 = at most n),
  * "embed_waste" (a 2D filter shape without a compiled instance runs inside the smallest compiled
  * square box that holds it, zero-padded; a value n >= 0 allows that only while the box has at most
