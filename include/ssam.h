@@ -21,8 +21,10 @@
  *   - Boundary rule: a read outside the grid gives 0 (SSAM_BOUNDARY_ZERO) or the value of
  *     the nearest grid point, every coordinate clamped on its own (SSAM_BOUNDARY_CLAMP).
  *     The paper does not state a rule; these are the two its comparison libraries use.
- *   - Results are deterministic run to run (no atomics); the order of additions differs
- *     from a sequential sum, so results agree with a reference to rounding, not bitwise.
+ *   - Results are deterministic run to run (the filter and stencil kernels use no atomics; the
+ *     one-pass scan hands out work through an atomic counter but combines partial sums in a fixed
+ *     order); the order of additions differs from a sequential sum, so results agree with a
+ *     reference to rounding, not bitwise.
  *   - Thread safety: calls may be made from several host threads on different streams.
  *   - The compute entry points only enqueue kernels: no allocation, no memset, no synchronisation.
  *     They may therefore be recorded by stream capture into a HIP graph and replayed (the host
@@ -41,12 +43,13 @@ extern "C" {
 typedef enum {
     SSAM_OK = 0,
     SSAM_ERR_NULL = 1,   /* a required pointer is NULL                                    */
-    SSAM_ERR_DIM = 2,    /* W, H or D not positive, or the grid exceeds 2^31-1 elements;
+    SSAM_ERR_DIM = 2,    /* W, H or D not positive or above SSAM_MAX_EXTENT, the grid exceeds
+                            2^31-1 elements, or its tile plan exceeds what one launch holds
+                            (3D grids of extreme aspect ratio, e.g. 1 x 2^30 x 2);
                             scan / probes: count out of range, misaligned pointer,
                             scratch or workspace too small                                */
     SSAM_ERR_SHAPE = 3,  /* filter / radius not positive, anchor outside the filter, or
-                            larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0; a
-                            dense coefficient box too large for any kernel (ssam_stencil3d) */
+                            larger than SSAM_MAX_FILTER / SSAM_MAX_RADIUS; steps < 0      */
     SSAM_ERR_ENUM = 4,   /* unknown dtype or boundary value                               */
     SSAM_ERR_ALIAS = 5,  /* input and output buffers overlap                              */
     SSAM_ERR_HIP = 6     /* a HIP runtime call failed (no device, launch failure)         */
@@ -57,6 +60,7 @@ typedef enum { SSAM_BOUNDARY_ZERO = 0, SSAM_BOUNDARY_CLAMP = 1 } ssam_boundary;
 
 #define SSAM_MAX_FILTER 32   /* largest filter width or height accepted by ssam_conv2d   */
 #define SSAM_MAX_RADIUS 8    /* largest stencil radius per axis                          */
+#define SSAM_MAX_EXTENT (1 << 30)   /* largest W, H or D (and W*H*D at most 2^31-1)      */
 
 /* 2D filter (paper Sec. 2.1; Listing 1 evaluates it without flipping the filter):
  *     out[y][x] = sum_{n<N} sum_{m<M}  h_filter[n*M + m] * IN(x + m - ax, y + n - ay)
@@ -81,9 +85,9 @@ int ssam_stencil2d(const void *d_in, void *d_out, int W, int H,
  *     out[z][y][x] = sum  h_coef[((dz+rz)*(2ry+1) + (dy+ry))*(2rx+1) + (dx+rx)] * IN(x+dx, y+dy, z+dz)
  * with the same zero-means-no-tap rule; Above = dz -1, Below = dz +1.
  * Shapes with a compiled instance (or that fit zero-padded inside one: stars up to radius 4, boxes
- * up to radius 2) run on the register-cache kernels; any other runs on a direct one-point-per-thread
- * kernel whose coefficients travel in a 3584-byte argument block: a star of any radius fits, a
- * dense box must have (2rx+1)(2ry+1)(2rz+1) elements within that size, else SSAM_ERR_SHAPE. */
+ * up to radius 2) run on the register-cache kernels; any other, up to SSAM_MAX_RADIUS per axis, runs
+ * on a direct one-point-per-thread kernel (correct, not fast) whose taps travel in the launch
+ * arguments, in as many launches on hip_stream as the tap count needs. */
 int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
                    const void *h_coef, int rx, int ry, int rz,
                    int boundary, int dtype, void *hip_stream);

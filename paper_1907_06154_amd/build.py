@@ -22,9 +22,22 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
 
 
-def _compile(src: str, extra) -> str:
+def _up_to_date(obj: str) -> bool:
+    """True when obj is newer than every file its dependency list (written by -MD) names."""
+    dep = obj + ".d"
+    if not (os.path.exists(obj) and os.path.exists(dep)):
+        return False
+    t = os.path.getmtime(obj)
+    words = open(dep).read().replace("\\\n", " ").split()
+    files = [w for w in words[1:] if not w.endswith(":")]
+    return all(os.path.exists(f) and os.path.getmtime(f) <= t for f in files)
+
+
+def _compile(src: str, extra, incremental: bool = False) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = ["hipcc", *FLAGS, *extra, "-c", src, "-o", obj]
+    if incremental and _up_to_date(obj):
+        return obj
+    cmd = ["hipcc", *FLAGS, *extra, "-MD", "-MF", obj + ".d", "-c", src, "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{res.stdout}\n{res.stderr}")
@@ -35,11 +48,13 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB) -> str:
+def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB, incremental: bool = False) -> str:
+    """incremental: recompile only the translation units whose sources or headers changed since
+    their object was written (a developer's shortcut; the default compiles everything)."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(lambda s: _compile(s, list(extra)), srcs))
+        objs = list(pool.map(lambda s: _compile(s, list(extra), incremental), srcs))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     subprocess.run(cmd, check=True)
     if verbose:
@@ -48,7 +63,7 @@ def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB) -> str
 
 
 if __name__ == "__main__":
-    # python -m paper_1907_06154_amd.build [output.so] [-DNAME ...]   (extra defines: experiments)
+    # python -m paper_1907_06154_amd.build [output.so] [-DNAME ...] [--incremental]   (extra defines: experiments)
     args = sys.argv[1:]
     out = next((a for a in args if a.endswith(".so")), LIB)
-    build(verbose=True, extra=[a for a in args if a.startswith("-D")], lib=out)
+    build(verbose=True, extra=[a for a in args if a.startswith("-D")], lib=out, incremental="--incremental" in args)

@@ -47,21 +47,25 @@ Tuning current_tuning()
 // ---- direct fallback kernel -------------------------------------------------------------
 // One output point per thread, taps read straight from global memory (cached).  It keeps the
 // ABI total: any filter or stencil shape without a compiled register-cache instance runs
-// here.  Coefficients travel in the kernel argument block, dense [K][N][M] or, for star
-// shapes, as three lines (z line, y line, x line; the centre sits in the z line).
+// here.  The taps travel in the kernel-argument block as a list of (coefficient, offset) pairs --
+// for a stencil only the non-zero ones, so a star of any radius is a short list.  A list too long
+// for one argument block is evaluated by several launches on the same stream, the first writing
+// the partial sum of its part, every later one adding its own part to what the output holds
+// (each thread only ever touches its own output element).
 constexpr int kGenericBytes = 3584;
 
 template <typename T>
 struct GenericArgs {
+    static constexpr int kCap = kGenericBytes / (sizeof(T) + sizeof(int));
     const T* in;
     T* out;
     int W, H, D;
-    int M, N, K;       // box extents (x, y, z)
-    int ax, ay, az;    // anchor
     int boundary;
-    int star;          // 1: coefficients are the three axis lines
-    int skip_zero;     // 1: an exactly-zero coefficient is not a tap
-    T w[kGenericBytes / sizeof(T)];
+    int ntaps;         // taps in this launch
+    int accumulate;    // 1: add to the value the output already holds
+    long long nblocks; // blocks of 64 x 4 points in the grid
+    T w[kCap];
+    int off[kCap];     // dx, dy, dz as signed bytes 0, 1, 2
 };
 
 template <typename T>
@@ -80,51 +84,23 @@ __device__ __forceinline__ T fetch(const GenericArgs<T>& a, int x, int y, int z)
 template <typename T>
 __global__ __launch_bounds__(256) void generic_kernel(const GenericArgs<T> a)
 {
-    // blocks of 64 x 4 points, numbered x fastest in one grid dimension (the other two are too short
-    // for tall grids)
-    const unsigned nbx = (unsigned)(a.W + 63) / 64, nby = (unsigned)(a.H + 3) / 4;
-    const unsigned b = blockIdx.x;
-    const int x = (int)(b % nbx) * 64 + (threadIdx.x & 63);
-    const int y = (int)((b / nbx) % nby) * 4 + (threadIdx.x >> 6);
-    const int z = (int)(b / nbx / nby);
-    if (x >= a.W || y >= a.H) return;
-    T sum = T(0);
-    if (a.star) {
-        for (int k = 0; k < a.K; ++k) {
-            const T c = a.w[k];
-            if (a.skip_zero && c == T(0)) continue;
-            sum = fma_t(c, fetch(a, x, y, z + k - a.az), sum);
+    // blocks of 64 x 4 points, numbered x fastest; the launched blocks stride over them (a tall
+    // or deep grid has more of them than one launch dimension takes)
+    const long long nbx = (a.W + 63) / 64, nby = (a.H + 3) / 4;
+    for (long long b = blockIdx.x; b < a.nblocks; b += gridDim.x) {
+        const int x = (int)(b % nbx) * 64 + (threadIdx.x & 63);
+        const int y = (int)((b / nbx) % nby) * 4 + (threadIdx.x >> 6);
+        const int z = (int)(b / nbx / nby);
+        if (x >= a.W || y >= a.H) continue;
+        T* o = a.out + ((size_t)z * a.H + y) * a.W + x;
+        T sum = a.accumulate ? *o : T(0);
+        for (int t = 0; t < a.ntaps; ++t) {
+            const int off = a.off[t];
+            sum = fma_t(a.w[t], fetch(a, x + (int)(signed char)(off & 0xff), y + (int)(signed char)((off >> 8) & 0xff),
+                                      z + (int)(signed char)((off >> 16) & 0xff)), sum);
         }
-        for (int n = 0; n < a.N; ++n) {
-            const T c = a.w[a.K + n];
-            if (n == a.ay || (a.skip_zero && c == T(0))) continue;
-            sum = fma_t(c, fetch(a, x, y + n - a.ay, z), sum);
-        }
-        for (int m = 0; m < a.M; ++m) {
-            const T c = a.w[a.K + a.N + m];
-            if (m == a.ax || (a.skip_zero && c == T(0))) continue;
-            sum = fma_t(c, fetch(a, x + m - a.ax, y, z), sum);
-        }
-    } else {
-        for (int k = 0; k < a.K; ++k)
-            for (int n = 0; n < a.N; ++n)
-                for (int m = 0; m < a.M; ++m) {
-                    const T c = a.w[(k * a.N + n) * a.M + m];
-                    if (a.skip_zero && c == T(0)) continue;
-                    sum = fma_t(c, fetch(a, x + m - a.ax, y + n - a.ay, z + k - a.az), sum);
-                }
+        *o = sum;
     }
-    a.out[((size_t)z * a.H + y) * a.W + x] = sum;
-}
-
-template <typename T>
-bool is_star(const T* c, int M, int N, int K, int ax, int ay, int az)
-{
-    for (int k = 0; k < K; ++k)
-        for (int n = 0; n < N; ++n)
-            for (int m = 0; m < M; ++m)
-                if (c[(k * N + n) * M + m] != T(0) && ((k != az) + (n != ay) + (m != ax)) > 1) return false;
-    return true;
 }
 
 // Largest number of simultaneously non-zero offset components among the taps (0..3).
@@ -143,14 +119,6 @@ int tap_budget(const T* c, int M, int N, int K, int ax, int ay, int az)
 }
 
 template <typename T>
-bool generic_fits(const T* c, int M, int N, int K, int ax, int ay, int az, bool allow_star)
-{
-    const size_t cap = kGenericBytes / sizeof(T);
-    if ((size_t)M * N * K <= cap) return true;
-    return allow_star && is_star(c, M, N, K, ax, ay, az) && (size_t)(M + N + K) <= cap;
-}
-
-template <typename T>
 hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, int M, int N, int K, int ax,
                           int ay, int az, int boundary, bool skip_zero, hipStream_t stream)
 {
@@ -158,24 +126,30 @@ hipError_t launch_generic(const T* in, T* out, int W, int H, int D, const T* c, 
     a.in = in;
     a.out = out;
     a.W = W; a.H = H; a.D = D;
-    a.M = M; a.N = N; a.K = K;
-    a.ax = ax; a.ay = ay; a.az = az;
     a.boundary = boundary;
-    a.skip_zero = skip_zero ? 1 : 0;
-    const size_t cap = kGenericBytes / sizeof(T);
-    if ((size_t)M * N * K <= cap) {
-        a.star = 0;
-        for (int i = 0; i < M * N * K; ++i) a.w[i] = c[i];
-    } else {
-        a.star = 1;
-        for (int k = 0; k < K; ++k) a.w[k] = c[(k * N + ay) * M + ax];
-        for (int n = 0; n < N; ++n) a.w[K + n] = c[(az * N + n) * M + ax];
-        for (int m = 0; m < M; ++m) a.w[K + N + m] = c[(az * N + ay) * M + m];
-    }
-    const long long blocks = (long long)ceil_div(W, 64) * ceil_div(H, 4) * D;   // W*H*D < 2^31, so this fits
-    if (blocks > 2147483647LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(generic_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    a.nblocks = (long long)ceil_div(W, 64) * ceil_div(H, 4) * D;
+    const unsigned grid = (unsigned)(a.nblocks < (1LL << 20) ? a.nblocks : (1LL << 20));
+    a.ntaps = 0;
+    a.accumulate = 0;
+    auto flush = [&]() {
+        hipLaunchKernelGGL(generic_kernel<T>, dim3(grid), dim3(256), 0, stream, a);
+        a.ntaps = 0;
+        a.accumulate = 1;
+        return hipGetLastError();
+    };
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            for (int m = 0; m < M; ++m) {
+                const T v = c[((size_t)k * N + n) * M + m];
+                if (skip_zero && v == T(0)) continue;
+                a.w[a.ntaps] = v;
+                a.off[a.ntaps] = ((m - ax) & 0xff) | (((n - ay) & 0xff) << 8) | (((k - az) & 0xff) << 16);
+                if (++a.ntaps == GenericArgs<T>::kCap)
+                    if (hipError_t e = flush()) return e;
+            }
+    if (a.ntaps > 0 || !a.accumulate)      // the last part; a stencil without any tap still writes zeros
+        if (hipError_t e = flush()) return e;
+    return hipSuccess;
 }
 
 // ---- plain copy (measurement aid) ---------------------------------------------------------
@@ -199,6 +173,7 @@ int check_enums(int boundary, int dtype)
 int check_dims(int W, int H, int D)
 {
     if (W <= 0 || H <= 0 || D <= 0) return SSAM_ERR_DIM;
+    if (W > SSAM_MAX_EXTENT || H > SSAM_MAX_EXTENT || D > SSAM_MAX_EXTENT) return SSAM_ERR_DIM;
     if ((long long)W * H * D > 2147483647LL) return SSAM_ERR_DIM;
     return SSAM_OK;
 }
@@ -210,6 +185,13 @@ bool overlap(const void* a, const void* b, size_t bytes)
 }
 
 size_t elem(int dtype) { return dtype == SSAM_F32 ? 4 : 8; }
+
+// A launcher reports a tile plan that no launch can hold (more blocks than a grid dimension takes:
+// grids of extreme aspect ratio) as hipErrorInvalidConfiguration, before it launches anything.
+int status_of(hipError_t e)
+{
+    return e == hipSuccess ? SSAM_OK : e == hipErrorInvalidConfiguration ? SSAM_ERR_DIM : SSAM_ERR_HIP;
+}
 
 // ---- dispatch ---------------------------------------------------------------------------
 template <typename T>
@@ -247,7 +229,7 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
     }
     if (inst) {
         if (name) *name = inst->name;
-        return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        return status_of(inst->launch(p, tu, geo, dry));
     }
     // No instance of this exact shape (a non-square filter, an anchor off the centre, unequal
     // radii): embed it in the smallest compiled square box whose centre anchor leaves enough room
@@ -276,7 +258,7 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
             q.ax = q.ay = c;
             q.w = padded.data();
             if (name) *name = std::string(box->name) + "+embedded";
-            return box->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;   // weights are copied into the launch arguments
+            return status_of(box->launch(q, tu, geo, dry));   // weights are copied into the launch arguments
         }
     }
     if (name) *name = "generic_direct";
@@ -284,17 +266,13 @@ int run2d(const Problem2D& p, bool stencil_semantics, Geometry* geo, bool dry, s
         *geo = Geometry();
         geo->blocks = ceil_div(p.W, 64) * ceil_div(p.H, 4);
     }
-    bool fits = p.dtype == SSAM_F32
-                    ? generic_fits<float>((const float*)p.w, p.M, p.N, 1, p.ax, p.ay, 0, stencil_semantics)
-                    : generic_fits<double>((const double*)p.w, p.M, p.N, 1, p.ax, p.ay, 0, stencil_semantics);
-    if (!fits) return SSAM_ERR_SHAPE;
     if (dry) return SSAM_OK;
     hipError_t e = p.dtype == SSAM_F32
                        ? launch_generic<float>((const float*)p.in, (float*)p.out, p.W, p.H, 1, (const float*)p.w, p.M,
                                                p.N, 1, p.ax, p.ay, 0, p.boundary, stencil_semantics, p.stream)
                        : launch_generic<double>((const double*)p.in, (double*)p.out, p.W, p.H, 1, (const double*)p.w,
                                                 p.M, p.N, 1, p.ax, p.ay, 0, p.boundary, stencil_semantics, p.stream);
-    return e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    return status_of(e);
 }
 
 template <typename T>
@@ -357,7 +335,7 @@ int run_fused(const Problem3D& p, int max_sweeps, Geometry* geo, bool dry, std::
             if (name) *name = inst->name;
             e = inst->launch(p, tu, geo, dry);
         }
-        *rc = e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        *rc = status_of(e);
         return sweeps;
     }
     return 0;
@@ -380,7 +358,7 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
     }
     if (inst) {
         if (name) *name = inst->name;
-        return inst->launch(p, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+        return status_of(inst->launch(p, tu, geo, dry));
     }
     // No instance for these radii: embed the coefficient box, zero-padded, in the cheapest compiled
     // shape with equal radii that covers it (a star in a wider star, anything in a box).
@@ -413,7 +391,7 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
             q.rx = q.ry = q.rz = R;
             q.c = padded.data();
             if (name) *name = std::string(cube->name) + "+embedded";
-            return cube->launch(q, tu, geo, dry) == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+            return status_of(cube->launch(q, tu, geo, dry));
         }
     }
     if (name) *name = "generic_direct";
@@ -422,9 +400,6 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
         geo->blocks = ceil_div(p.W, 64) * ceil_div(p.H, 4) * p.D;
     }
     const int M = 2 * p.rx + 1, N = 2 * p.ry + 1, K = 2 * p.rz + 1;
-    bool fits = p.dtype == SSAM_F32 ? generic_fits<float>((const float*)p.c, M, N, K, p.rx, p.ry, p.rz, true)
-                                    : generic_fits<double>((const double*)p.c, M, N, K, p.rx, p.ry, p.rz, true);
-    if (!fits) return SSAM_ERR_SHAPE;
     if (dry) return SSAM_OK;
     hipError_t e = p.dtype == SSAM_F32
                        ? launch_generic<float>((const float*)p.in, (float*)p.out, p.W, p.H, p.D, (const float*)p.c, M,
@@ -432,7 +407,7 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
                        : launch_generic<double>((const double*)p.in, (double*)p.out, p.W, p.H, p.D,
                                                 (const double*)p.c, M, N, K, p.rx, p.ry, p.rz, p.boundary, true,
                                                 p.stream);
-    return e == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
+    return status_of(e);
 }
 
 int validate_conv(const void* in, const void* out, int W, int H, const void* f, int M, int N, int* ax, int* ay,

@@ -1,4 +1,4 @@
-// Host-side types shared by the dispatcher (ssam_api.cpp) and the kernel translation units.
+// Host-side types shared by the dispatcher (ssam_api.hip) and the kernel translation units.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -98,7 +98,8 @@ struct Register3D {
     explicit Register3D(const Instance3D& i) { registry3d().push_back(i); }
 };
 
-inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+// a, b > 0; the sum is formed in 64 bits so that extents near 2^31 do not wrap
+inline int ceil_div(int a, int b) { return (int)(((long long)a + b - 1) / b); }
 
 inline bool pointers_aligned(const void* a, const void* b, size_t bytes)
 {
@@ -186,9 +187,19 @@ inline int balanced_planes(int D, long tiles_xy, int slots, int preferred, int f
     return planes;
 }
 
+// A launch dimension holds fewer than 2^32 threads: with blocks of at most 1024 threads that is 2^22
+// blocks, whatever the kernel.  Launchers return hipErrorInvalidConfiguration for a plan beyond it.
+constexpr long kMaxBlocks = (1L << 22) - 8;
+inline bool launchable(const Geometry& g) { return g.blocks > 0 && g.blocks <= kMaxBlocks && g.tiles <= 4 * kMaxBlocks; }
+
 inline void plan_blocks(Geometry* g, int remap_override)
 {
     g->tiles = (long)g->strips_x * g->tiles_y * g->tiles_z;
+    if (g->tiles > 4 * kMaxBlocks) {   // not launchable: leave a block count that says so
+        g->xcd_remap = 0;
+        g->blocks = -1;
+        return;
+    }
     int blocks = (int)((g->tiles + 3) / 4);
     g->xcd_remap = remap_override < 0 ? 1 : (remap_override ? 1 : 0);
     if (g->xcd_remap) blocks = ceil_div(blocks, 8) * 8;

@@ -5,7 +5,9 @@
 // its rows P at a time (the sliding window of Sec. 4.2, extended to a march: after each
 // group of P window positions the last N-1 cached rows are kept and P new rows are loaded,
 // so the vertical halo is read once per tile rather than once per P rows).
-// No LDS and no barrier: waves are independent (Sec. 4.5).
+// Waves are independent (Sec. 4.5): the vector-unit engine uses no LDS and no barrier; the
+// matrix-core engine builds its filter table in LDS once per workgroup (one barrier, before the
+// march) and shares nothing else.
 #pragma once
 #include "ssam_device.h"
 #include "ssam_host.h"
@@ -224,12 +226,14 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
         // in step and finish together, which matters more than the re-read rows, which hit in L2
         rows = 2 * (N - 1) > P ? 2 * (N - 1) : P;
     }
+    while ((long)g.strips_x * ceil_div(pr.H, rows) > 4 * kMaxBlocks) rows *= 2;   // very tall grids: fewer, taller tiles
     rows = ceil_div(rows, P) * P;
     if (rows > ceil_div(pr.H, P) * P) rows = ceil_div(pr.H, P) * P;
     g.rows_per_wave = rows;
     g.tiles_y = ceil_div(pr.H, rows);
     plan_blocks(&g, tu.xcd_remap);
     if (geo) *geo = g;
+    if (!launchable(g)) return hipErrorInvalidConfiguration;
     if (dry_run) return hipSuccess;
 
     Args2D<T, Mask::kNW> a;

@@ -275,6 +275,7 @@ hipError_t launch2d_fused(const Problem2D& pr, const Tuning& tu, Geometry* geo, 
     g.tiles_y = ceil_div(pr.H, rows);
     plan_blocks(&g, tu.xcd_remap);
     if (geo) *geo = g;
+    if (!launchable(g)) return hipErrorInvalidConfiguration;
     if (dry_run) return hipSuccess;
 
     Args2D<T, Mask::kNW> a;

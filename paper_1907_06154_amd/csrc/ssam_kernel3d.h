@@ -262,6 +262,7 @@ hipError_t launch3d(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool d
     g.tiles_z = ceil_div(LD, planes);
     plan_blocks(&g, tu.xcd_remap);
     if (geo) *geo = g;
+    if (!launchable(g)) return hipErrorInvalidConfiguration;
     if (dry_run) return hipSuccess;
 
     Args3D<T, Mask0::kNW> a;

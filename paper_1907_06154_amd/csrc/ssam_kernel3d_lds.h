@@ -223,6 +223,7 @@ hipError_t launch3d_lds(const Problem3D& pr, const Tuning& tu, Geometry* geo, bo
     g.xcd_remap = tu.xcd_remap < 0 ? 1 : (tu.xcd_remap ? 1 : 0);
     g.blocks = g.xcd_remap ? ceil_div((int)g.tiles, kXcds) * kXcds : (int)g.tiles;
     if (geo) *geo = g;
+    if (!launchable(g)) return hipErrorInvalidConfiguration;
     if (dry_run) return hipSuccess;
 
     Args3D<T, Mask0::kNW> a;

@@ -193,13 +193,45 @@ def test_shape_classification(L):
         assert name == "generic_direct"
     finally:
         ssam.ssam_set_tuning("embed_waste", -1)
-    # a dense 3D box too large for the argument block is refused
-    with pytest.raises(ssam.SsamError):
-        ssam.ssam_describe("stencil3d", (32, 32, 32), np.ones((9, 9, 9), dtype=np.float64), "zero")
-    # ... but the same radii as a star fit
+    # every shape up to the advertised limits is accepted: the direct kernel takes a tap list of any
+    # length (several launches), so neither a dense 17^3 box nor a 32x32 filter is refused
+    for box in (np.ones((9, 9, 9), dtype=np.float64), np.ones((17, 17, 17), dtype=np.float64), np.ones((17, 17, 17), dtype=np.float32)):
+        name, _ = parse(ssam.ssam_describe("stencil3d", (32, 32, 32), box, "zero"))
+        assert name == "generic_direct"
     star = np.zeros((17, 17, 17)); star[8, 8, :] = 1; star[8, :, 8] = 1; star[:, 8, 8] = 1
     name, _ = parse(ssam.ssam_describe("stencil3d", (32, 32, 32), star, "zero"))
     assert name == "generic_direct"
+    for dt in (np.float32, np.float64):
+        for shape in ((32, 32), (30, 30), (22, 22), (32, 1), (1, 32)):
+            name, _ = parse(ssam.ssam_describe("conv2d", (100, 100), np.ones(shape, dtype=dt), "clamp"))
+            assert name == "generic_direct" or name.endswith("+embedded") or "_M" in name, name
+
+
+def test_extreme_extents_plan_or_refuse(L):
+    """Extents near the limits: the planner's arithmetic must not wrap.  Every extent up to
+    SSAM_MAX_EXTENT (2^30) with W*H*D <= 2^31-1 either gets a plan with positive counts that
+    covers the grid, or SSAM_ERR_DIM; anything above is SSAM_ERR_DIM."""
+    big = 1 << 30
+    f = np.ones((3, 3), dtype=np.float32)
+    for W, H in ((1, big), (big, 1), (2, big - 1), (big - 1, 2), (3, 715827882)):
+        name, g = parse(ssam.ssam_describe("conv2d", (H, W), f, "clamp"))
+        assert g["valid_lanes"] > 0 and g["strips_x"] > 0 and g["tiles_y"] > 0 and g["blocks"] > 0, (W, H, g)
+        assert g["strips_x"] * g["valid_lanes"] * g["V"] >= W and g["tiles_y"] * g["rows_per_wave"] >= H
+        assert g["tiles"] == g["strips_x"] * g["tiles_y"] and g["blocks"] * 4 >= g["tiles"] and g["blocks"] < (1 << 22)
+    buf = ctypes.create_string_buffer(512)
+    for W, H, D in ((2147483647, 1, 1), (1, 2147483647, 1), (1, 1, 2147483647), (big + 1, 1, 1)):
+        c3 = np.ones(27, dtype=np.float64)
+        assert L.ssam_describe(2, W, H, D, c3.ctypes.data, 1, 1, 1, 0, 1, buf, 512) == 2, (W, H, D)
+        assert L.ssam_conv2d(FAKE_A, FAKE_B, W, H, f.ctypes.data, 3, 3, -1, -1, 1, 0, None) == 2 or D > 1
+    # 3D plans of extreme aspect ratio: a plan with positive counts, or SSAM_ERR_DIM -- never a wrapped one
+    c3 = np.ones((3, 3, 3), dtype=np.float64)
+    for shape in ((2, big, 1), (big, 1, 2), (1, 2, big), (2, 1, big)):
+        try:
+            name, g = parse(ssam.ssam_describe("stencil3d", shape, c3, "zero"))
+        except ssam.SsamError as e:
+            assert e.status == 2
+            continue
+        assert g["blocks"] > 0 and g["tiles"] > 0 and g["strips_x"] > 0 and g["tiles_y"] > 0 and g["tiles_z"] > 0, (shape, g)
 
 
 def test_fused_sweep_plan(L):

@@ -462,6 +462,33 @@ def test_direct_kernel_on_tall_and_deep_grids(ssam):
     assert_parity(got, oracle.stencil(fld, coef, "zero"), coef, 1.0, "deep grid, direct kernel")
 
 
+def test_direct_kernel_takes_every_shape_up_to_the_limits(ssam):
+    """Shapes whose tap list exceeds one argument block run as several launches, every later one
+    adding its part to the output: the largest filter and the largest dense boxes the header
+    advertises, both precisions, both boundary rules."""
+    for dt in (np.float32, np.float64):
+        img = wl.uniform_field((45, 150), 0.0, 1.0, 611, dt)
+        for (M, N) in ((32, 32), (30, 31), (22, 22), (32, 1)):
+            filt = wl.seeded_filter(M, N, 612 + M, dt)
+            for bnd in ("clamp", "zero"):
+                print(f"direct conv2d {np.dtype(dt).name} {M}x{N} {bnd}", flush=True)
+                got = host(ssam.ssam_conv2d(dev(img), filt, bnd))
+                assert_parity(got, oracle.conv2d(img, filt, bnd), filt, 1.0, f"direct {M}x{N} {bnd}")
+        fld = wl.uniform_field((11, 9, 70), -1.0, 1.0, 613, dt)
+        for r in ((4, 4, 4), (8, 8, 8), (8, 3, 5)):
+            coef = wl.seeded_coefficients(wl.mask_box(*r), 614, dt)
+            for bnd in ("zero", "clamp"):
+                print(f"direct stencil3d {np.dtype(dt).name} box r{r} {bnd}", flush=True)
+                assert ssam.ssam_describe("stencil3d", fld.shape, coef, bnd).split()[0] == "generic_direct"
+                got = host(ssam.ssam_stencil3d(dev(fld), coef, bnd))
+                assert_parity(got, oracle.stencil(fld, coef, bnd), coef, 1.0, f"direct box r{r} {bnd}")
+        # nothing but zeros: no tap at all, the output is zero everywhere (not left unwritten)
+        none = np.zeros((17, 17, 17), dtype=dt)
+        out = torch.full(fld.shape, float("nan"), dtype=torch.from_numpy(fld).dtype, device="cuda")
+        got = host(ssam.ssam_stencil3d(dev(fld), none, "zero", d_out=out))
+        assert np.array_equal(got, np.zeros_like(fld))
+
+
 @pytest.mark.parametrize("shape,mask", [((200, 512), wl.mask_star(1, 1)), ((40, 64, 128), wl.mask_star(1, 1, 1)),
                                         ((33, 40, 130), wl.mask_star(4, 4, 4))])
 def test_iterate_can_be_captured_in_a_hip_graph(ssam, shape, mask):
