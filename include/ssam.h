@@ -180,6 +180,20 @@ int ssam_scan(const void *d_in, void *d_out, long long n, int dtype,
  * suffices or the arguments are invalid). */
 size_t ssam_scan_workspace_bytes(long long n, int dtype);
 
+/* ssam_scan for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * ssam_scan on the same arguments (same kernels, same schedules), with the workspace taken from an
+ * array the library holds in device memory (about 2.1 MiB on every GPU it runs on, until the
+ * process ends) instead of a d_work argument.  The call allocates nothing and frees nothing; its
+ * first call on a device looks the array's address up once.  What must start at zero is cleared by
+ * a kernel on hip_stream, so earlier calls leave nothing behind.  All calls on one GPU share the
+ * one array: two calls whose work overlaps in time on the same GPU (different streams, or several
+ * host threads) race -- serialise them, or give ssam_scan workspaces of their own.
+ * n above SSAM_SCAN_STATIC_MAX_ELEMENTS gives SSAM_ERR_DIM (use ssam_scan); the other errors are
+ * ssam_scan's. */
+#define SSAM_SCAN_STATIC_MAX_ELEMENTS (1LL << 32)
+int ssam_scan_static(const void *d_in, void *d_out, long long n, int dtype, void *hip_stream);
+
 /* Measurement aid: copies nbytes (a multiple of 16; both pointers 16-byte aligned, not
  * overlapping) from d_in to d_out with a plain grid-stride 16-bytes-per-lane kernel on hip_stream.
  * It is a reference rate for one-read-one-write kernels (not a ceiling: kernels whose waves move

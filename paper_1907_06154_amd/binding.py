@@ -21,7 +21,7 @@ SSAM_BOUNDARY_ZERO, SSAM_BOUNDARY_CLAMP = 0, 1
 BOUNDARY = {"zero": SSAM_BOUNDARY_ZERO, "clamp": SSAM_BOUNDARY_CLAMP}
 EXPORTS = ["ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
            "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy", "ssam_probe_latency",
-           "ssam_scan", "ssam_scan_workspace_bytes"]
+           "ssam_scan", "ssam_scan_workspace_bytes", "ssam_scan_static"]
 
 
 class SsamError(RuntimeError):
@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.ssam_probe_latency.restype = ci
         L.ssam_scan.argtypes = [vp, vp, ctypes.c_longlong, ci, vp, ctypes.c_size_t, vp]
         L.ssam_scan_workspace_bytes.argtypes = [ctypes.c_longlong, ci]
+        L.ssam_scan_static.argtypes = [vp, vp, ctypes.c_longlong, ci, vp]
         for name in EXPORTS:
             if name not in ("ssam_status_string", "ssam_scan_workspace_bytes"):
                 getattr(L, name).restype = ci
@@ -253,6 +254,19 @@ def ssam_scan(d_in, d_out=None, d_work=None, stream=None):
     wp, wb = (d_work.data_ptr(), d_work.numel() * d_work.element_size()) if d_work is not None else (None, 0)
     _check(lib().ssam_scan(d_in.data_ptr() if n else None, d_out.data_ptr() if n else None, n, code,
                            wp, wb, _stream_ptr(stream)), "ssam_scan")
+    return d_out
+
+
+def ssam_scan_static(d_in, d_out, stream=None):
+    """ssam_scan with the workspace held by the library (no allocation in the call): both tensors
+    are the caller's."""
+    _device_tensor(d_in, "d_in")
+    _device_tensor(d_out, "d_out")
+    if d_in.dim() != 1 or d_out.shape != d_in.shape or d_out.dtype != d_in.dtype:
+        raise ValueError("ssam_scan_static takes two 1D tensors of the same shape and dtype")
+    n = d_in.numel()
+    _check(lib().ssam_scan_static(d_in.data_ptr() if n else None, d_out.data_ptr() if n else None, n,
+                                  _dtype_code(d_in), _stream_ptr(stream)), "ssam_scan_static")
     return d_out
 
 

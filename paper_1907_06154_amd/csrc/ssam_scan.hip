@@ -563,10 +563,53 @@ int launch_scan(const void* d_in, void* d_out, void* d_work, long long n, int dt
     return hipGetLastError() == hipSuccess ? SSAM_OK : SSAM_ERR_HIP;
 }
 
+// ---- workspace held by the library (ssam_scan_static) ----------------------------------------
+// Sized for the largest workspace any schedule asks for: the one-pass layout with the most
+// segments it accepts.  Every GPU the library runs on holds its own copy until the process ends.
+constexpr long long kStaticWords = kWsA + kChainMaxSegments;
+static __device__ __align__(256) Word scratch[kStaticWords];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_of_device[kMaxDevices];
+
+// Device address of `scratch` on the current device (the array's name is only a host-side handle:
+// each GPU has its copy at an address of its own, looked up once per device).
+int static_scratch(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSAM_ERR_HIP;
+    void* p = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return SSAM_ERR_HIP;
+        }
+        g_scratch_of_device[dev].store(p, std::memory_order_release);   // every thread finds the same address
+    }
+    *out = p;
+    return SSAM_OK;
+}
+
 }  // namespace
 }  // namespace ssam
 
 extern "C" {
+
+int ssam_scan_static(const void* d_in, void* d_out, long long n, int dtype, void* hip_stream)
+{
+    using namespace ssam;
+    if (dtype != SSAM_F32 && dtype != SSAM_F64) return SSAM_ERR_ENUM;
+    if (n < 0 || n > SSAM_SCAN_STATIC_MAX_ELEMENTS) return SSAM_ERR_DIM;
+    if (n == 0) return SSAM_OK;
+    if (!d_in || !d_out) return SSAM_ERR_NULL;
+    if (ssam_scan_workspace_bytes(n, dtype) > sizeof(Word) * (size_t)kStaticWords) return SSAM_ERR_DIM;
+    void* ws = nullptr;
+    if (int e = static_scratch(&ws)) return e;
+    // ssam_scan clears what its kernels expect to start at zero (the one-pass schedule's counter,
+    // flag and published sums) with a kernel of its own on the same stream, so the contents the
+    // previous call left behind do not matter.
+    return ssam_scan(d_in, d_out, n, dtype, ws, sizeof(Word) * (size_t)kStaticWords, hip_stream);
+}
 
 size_t ssam_scan_workspace_bytes(long long n, int dtype)
 {
