@@ -34,7 +34,10 @@ def _up_to_date(obj: str) -> bool:
 
 
 def _compile(src: str, extra, incremental: bool = False) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    # objects of a build with extra defines live in a folder of their own
+    objdir = OBJ if not extra else OBJ + "_" + "".join(c if c.isalnum() else "_" for c in "".join(extra))
+    os.makedirs(objdir, exist_ok=True)
+    obj = os.path.join(objdir, os.path.basename(src) + ".o")
     if incremental and _up_to_date(obj):
         return obj
     cmd = ["hipcc", *FLAGS, *extra, "-MD", "-MF", obj + ".d", "-c", src, "-o", obj]

@@ -1,0 +1,378 @@
+// 3D star stencil of radius R, block-cooperative: the NW waves of a block are stacked in y on one
+// x-strip, share every input plane through LDS, and march along z with the output planes in
+// flight held in registers (z is the in-register direction, see ssam_kernel3d.h).
+//
+// What differs from ssam_kernel3d_lds.h, and why (measured on 512^3, radius 4, where that kernel
+// ran at 0.45 / 0.53 of the HBM peak with half its wave-cycles waiting):
+//   - No halo lanes.  A wave's 64 lanes own 64*V adjacent columns and store all of them.  The
+//     columns a wave needs beyond its own come from the staged plane in LDS, which holds the
+//     strip plus R columns on either side: lane 0 (lane 63) reads them, and the lane-to-lane
+//     shift takes them in as the value of the lane that does not exist -- a DPP whole-wave shift
+//     leaves the destination of a lane without a source untouched, so the shift writes into the
+//     register that already holds the halo columns.  No instruction is added for it, and a 512-
+//     column row is two (fp32) or four (fp64) full waves instead of five with 56 storing lanes.
+//   - The in-plane x taps multiply neighbouring INPUT columns, shifted in once per centre row
+//     (ceil(R/V) shifts of V values per side), instead of shifting partial sums per tap group:
+//     a star has x taps in the centre row of each window only.
+//   - The fetch is decoupled from the lane layout: the block's threads split the staged tile
+//     (NW*P + 2R rows of 64 + 2*ceil(R/V) 16-byte pieces) evenly, so every row is read as one
+//     contiguous run and the rows shared by the waves of a block are fetched once.
+//   - Planes travel from global memory straight into LDS (global_load_lds_dwordx4: every lane
+//     names its own 16 source bytes, the wave's 64 pieces land side by side in LDS), NBUF - 1
+//     plane-steps ahead of their use in a ring of NBUF buffers.  No register is spent on data in
+//     flight, so two plane-steps of arithmetic cover the memory latency where the register-staged
+//     kernel had less than one.  The block synchronises once per step: every wave waits until its
+//     own loads of the plane about to be used have landed (they complete in order, so a count of
+//     the younger requests that may stay outstanding is enough), then one barrier.
+//   - Boundary rule in the fetch.  Zero padding: a piece outside the grid is loaded from 16 zero
+//     bytes the library keeps in device memory (so every lane issues every load and the request
+//     counts are the same in all waves).  Clamp: row and plane indices are clamped; blocks whose
+//     tile reaches past the grid in x or y -- pieces left or right of the grid take the edge
+//     column of their row, which no plain load delivers -- stage through registers instead (one
+//     plane ahead).
+// Requirements (the launcher falls back to ssam3d_lds_kernel otherwise): W a multiple of V and
+// both base pointers 16-byte aligned.
+#pragma once
+#include "ssam_kernel3d_lds.h"
+
+namespace ssam {
+
+template <typename T>
+struct Piece16 {
+    static constexpr int V = 16 / (int)sizeof(T);
+    typedef typename VecOf<T, V>::type type;
+};
+
+// old where the lane has no source, else the value of the lane below / above (see the file header)
+__device__ __forceinline__ int shift_in_up(int v, int edge) { return __builtin_amdgcn_update_dpp(edge, v, 0x138, 0xf, 0xf, false); }
+__device__ __forceinline__ int shift_in_down(int v, int edge) { return __builtin_amdgcn_update_dpp(edge, v, 0x130, 0xf, 0xf, false); }
+__device__ __forceinline__ float shift_in_up(float v, float edge)
+{
+    return __builtin_bit_cast(float, shift_in_up(__builtin_bit_cast(int, v), __builtin_bit_cast(int, edge)));
+}
+__device__ __forceinline__ float shift_in_down(float v, float edge)
+{
+    return __builtin_bit_cast(float, shift_in_down(__builtin_bit_cast(int, v), __builtin_bit_cast(int, edge)));
+}
+__device__ __forceinline__ double shift_in_up(double v, double edge)
+{
+    Halves a = __builtin_bit_cast(Halves, v), e = __builtin_bit_cast(Halves, edge);
+    a.lo = shift_in_up(a.lo, e.lo);
+    a.hi = shift_in_up(a.hi, e.hi);
+    return __builtin_bit_cast(double, a);
+}
+__device__ __forceinline__ double shift_in_down(double v, double edge)
+{
+    Halves a = __builtin_bit_cast(Halves, v), e = __builtin_bit_cast(Halves, edge);
+    a.lo = shift_in_down(a.lo, e.lo);
+    a.hi = shift_in_down(a.hi, e.hi);
+    return __builtin_bit_cast(double, a);
+}
+
+// Waits until at most n of this wave's vector-memory requests are outstanding and every LDS
+// access of the wave is done, then joins the block's barrier.  One statement, so that nothing is
+// scheduled in between, and a compiler-level memory barrier.  (The fence of __syncthreads would
+// wait for ALL outstanding loads into LDS, which is exactly what the ring of buffers avoids.)
+template <int N>
+__device__ __forceinline__ void wait_and_sync_n()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_and_sync(int n)   // n block-uniform, 0 .. 31; rounded down to a multiple of 2
+{
+    switch (n >> 1) {
+#define SSAM_WS(k) case k: wait_and_sync_n<2 * k>(); break;
+        SSAM_WS(0) SSAM_WS(1) SSAM_WS(2) SSAM_WS(3) SSAM_WS(4) SSAM_WS(5) SSAM_WS(6) SSAM_WS(7)
+        SSAM_WS(8) SSAM_WS(9) SSAM_WS(10) SSAM_WS(11) SSAM_WS(12) SSAM_WS(13) SSAM_WS(14)
+#undef SSAM_WS
+        default: wait_and_sync_n<30>(); break;
+    }
+}
+
+// Every lane of the wave loads its own 16 bytes at `src`; the 64 pieces land side by side in LDS
+// from `lds_base` (wave-uniform) on, in lane order.  Completion is counted by vmcnt.
+__device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base)
+{
+    __builtin_amdgcn_global_load_lds(src, lds_base, 16, 0, 0);
+}
+
+// Sixteen zero bytes: what a piece outside the grid is loaded from under zero padding.
+static __device__ __align__(16) const unsigned kZeroPiece[4] = {0u, 0u, 0u, 0u};
+
+template <typename T, int P, int NW, int R, int NBUF, int NT>
+__global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) void ssam3d_star_kernel(
+    const Args3D<T, 3 * (2 * R + 1)> a)
+{
+    static_assert(NBUF == 3 || NBUF == 4, "a ring of three or four staged planes");
+    constexpr int PF = NBUF - 1;               // planes requested ahead
+    constexpr int V = Piece16<T>::V;
+    typedef typename Piece16<T>::type vec_t;
+    constexpr int NZ = 2 * R + 1;
+    constexpr int HC = (R + V - 1) / V;        // halo pieces on each side of a staged row
+    constexpr int RS = kWave + 2 * HC;         // pieces per staged row
+    constexpr int C = P + 2 * R;               // rows one wave evaluates from
+    constexpr int CB = NW * P + 2 * R;         // rows the block stages per plane
+    constexpr int TOTAL = CB * RS;             // pieces per staged plane
+    constexpr int NTHR = NW * kWave;
+    constexpr int NCH = (TOTAL + NTHR - 1) / NTHR;   // pieces one thread fetches per plane
+    constexpr int SLOTS = NCH * NTHR;          // LDS pieces per buffer (the last few are padding)
+    constexpr bool NT_STORE = (NT & kStreamStores) != 0;
+    static_assert((PF - 1) * (NCH + P) <= 30, "request count beyond what the wait encodes");
+
+    __shared__ vec_t stage[NBUF][SLOTS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lb = logical_block(blockIdx.x, a.blocks, a.xcd_remap);
+    if (lb >= a.tiles) return;                 // block-uniform: no wave is left waiting at a barrier
+    const int strip = lb % a.strips_x;
+    const int yblock = (lb / a.strips_x) % a.tiles_y;
+    const int ztile = lb / (a.strips_x * a.tiles_y);
+
+    const int W = a.W, H = a.H, D = a.D;
+    const int x0 = strip * (kWave * V);        // first column of the strip
+    const int xc = x0 + lane * V;              // first column this lane owns
+    const int yb0 = yblock * (NW * P);         // first output row of the block
+    const int y0 = yb0 + wave * P;             // first output row of this wave
+    const int z0 = ztile * a.planes_per_wave;
+    const int z1 = min(z0 + a.planes_per_wave, D);
+    const bool clamp = a.boundary == kClamp;
+    const T* __restrict__ in = a.in;
+    typedef Args3D<T, 3 * NZ> Args;
+    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));   // z line (centre at R), y line, x line
+    const size_t rowst = (size_t)a.stride_row, plane = (size_t)a.stride_plane;
+    const int nt = (z1 - z0) + 2 * R;          // input planes z0-R .. z1-1+R
+
+    // block-uniform: every staged piece lies inside the grid in x and y
+    const bool inside_xy = x0 - HC * V >= 0 && x0 + (kWave + HC) * V <= W && yb0 - R >= 0 && yb0 + NW * P + R <= H;
+
+    // ---- this thread's pieces of the staged plane (the same for every plane) ----------------------
+    unsigned off[NCH];      // byte offset of the piece inside a plane (row and column clamped into the grid);
+                            // 32 bits: the launcher sends larger planes to the other kernel
+    unsigned inb = 0;       // bit i: piece i exists and lies inside the grid in x and y
+    unsigned lft = 0, rgt = 0;   // bit i: piece i lies left / right of the grid
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int f = i * NTHR + tid;
+        const int row = f / RS, c = f - row * RS;
+        const int y = yb0 - R + row, x = x0 + (c - HC) * V;
+        const int yy = min(max(y, 0), H - 1), xx = min(max(x, 0), W - V);
+        off[i] = (unsigned)(((size_t)yy * rowst + xx) * sizeof(T));
+        inb |= (f < TOTAL && y >= 0 && y < H && x >= 0 && x < W) ? 1u << i : 0u;
+        lft |= (f < TOTAL && x < 0) ? 1u << i : 0u;
+        rgt |= (f < TOTAL && x >= W) ? 1u << i : 0u;
+    }
+
+    T acc[NZ][P][V];
+#pragma unroll
+    for (int s = 0; s < NZ; ++s)
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[s][p][j] = T(0);
+
+    const bool lane_stores = xc < W;
+    const int own = (wave * P) * RS + HC + lane;     // this lane's piece of the wave's first staged row
+    const int edge_l = (wave * P) * RS;              // the row's first piece; HC pieces of left halo
+    const int edge_r = (wave * P) * RS + HC + kWave; // HC pieces of right halo
+
+    // one step of the march: the staged plane `st` is input plane zin
+    auto step = [&](const vec_t* st, int zin) __attribute__((always_inline)) {
+        T sum[P][V];       // in-plane sums, seeded with the plane above's partial sums
+        // -- per window: z taps and the centre tap (in-flight plane s takes dz = R - s from this
+        //    input plane), then the x taps: neighbouring columns of the centre row, shifted in
+        //    from the lanes beside (the columns beyond the wave's own come in as the edge lanes'
+        //    "old" values)
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            T xs[(2 * HC + 1) * V];     // columns -HC*V .. (HC+1)*V - 1 relative to the lane's first
+            const vec_t v = st[own + (p + R) * RS];
+#pragma unroll
+            for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
+            const T* cen = &xs[HC * V];
+#pragma unroll
+            for (int s = 0; s < R; ++s)
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
+#pragma unroll
+            for (int j = 0; j < V; ++j) sum[p][j] = fma_into(cen[j], wts[R], acc[R + 1][p][j]);
+#pragma unroll
+            for (int s = R + 1; s < NZ - 1; ++s)
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[NZ - 1][p][j] = cen[j] * wts[0];
+#pragma unroll
+            for (int h = 1; h <= HC; ++h) {
+                const vec_t el = st[edge_l + (p + R) * RS + (HC - h)];   // same address in every lane: a broadcast
+                const vec_t er = st[edge_r + (p + R) * RS + (h - 1)];
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
+                    xs[(HC + h) * V + j] = shift_in_down(xs[(HC + h - 1) * V + j], (T)er[j]);
+                }
+            }
+#pragma unroll
+            for (int dx = -R; dx <= R; ++dx) {
+                if (dx == 0) continue;
+                const T wx = wts[2 * NZ + dx + R];
+#pragma unroll
+                for (int j = 0; j < V; ++j) sum[p][j] = fma_t(xs[HC * V + j + dx], wx, sum[p][j]);
+            }
+        }
+        // -- y taps: every staged row of the wave's window
+#pragma unroll
+        for (int k = 0; k < C; ++k) {
+            const vec_t v = st[own + k * RS];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int dy = k - R - p;
+                if (dy != 0 && dy >= -R && dy <= R) {
+                    const T wy = wts[NZ + dy + R];
+#pragma unroll
+                    for (int j = 0; j < V; ++j) sum[p][j] = fma_t((T)v[j], wy, sum[p][j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[R][p][j] = sum[p][j];
+
+        // output plane zin - R has now received its last contribution
+        const int zo = zin - R;
+        if (zo >= z0 && lane_stores) {
+            T* po = a.out + (size_t)zo * plane + (size_t)y0 * rowst + xc;
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+                if (y0 + p < H) store_vec<T, V, NT_STORE>(po + (size_t)p * rowst, acc[0][p]);
+        }
+    };
+
+    if (inside_xy || !clamp) {
+        // ---- planes straight into LDS, PF steps ahead --------------------------------------------
+        const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
+        auto request = [&](int z, int b) __attribute__((always_inline)) {
+            const bool plane_in = clamp || (z >= 0 && z < D);                     // block-uniform
+            const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
+            const unsigned keep = plane_in ? ~0u : 0u;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const char* src = pz + (off[i] & keep);
+                if (!inside_xy || (i + 1) * NTHR > TOTAL) src = (inb >> i) & 1u ? src : zero_src;
+                load16_to_lds(src, &stage[b][i * NTHR + wave * kWave]);
+            }
+        };
+        // a wave that stores all P rows issues P stores per step once output planes complete (step 2R on)
+        const bool full_rows = y0 + P <= H;
+#pragma unroll
+        for (int k = 0; k < PF; ++k)
+            if (k < nt) request(z0 - R + k, k);
+        int b = 0;
+        for (int t = 0; t < nt; ++t) {
+            // Requests younger than those of plane t, counting only what is certainly younger: the
+            // loads of planes t+1 .. t+PF-1 (issued in steps t-PF+1 .. t-1) and the stores of steps
+            // t-PF+1 .. t-1.
+            int younger = 0;
+#pragma unroll
+            for (int k = 1; k < PF; ++k) {
+                if (t + k < nt) younger += NCH;
+                if (full_rows && t - k >= 2 * R) younger += P;
+            }
+            wait_and_sync(younger);
+            // buffer (t + PF) % NBUF held plane t - 1, which every wave has finished reading
+            if (t + PF < nt) request(z0 - R + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
+            step(stage[b], z0 - R + t);
+            b = b + 1 == NBUF ? 0 : b + 1;
+        }
+    } else {
+        // ---- clamp rule, tile reaching past the grid in x or y: staged through registers ------
+        auto fetch = [&](int z, vec_t (&g)[NCH]) __attribute__((always_inline)) {
+            const char* pz = reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) g[i] = *reinterpret_cast<const vec_t*>(pz + off[i]);
+        };
+        auto stash = [&](int b, const vec_t (&g)[NCH]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                vec_t v = g[i];
+                const T first = v[0], last = v[V - 1];
+                const unsigned lm = (lft >> i) & 1u ? ~0u : 0u, rm = (rgt >> i) & 1u ? ~0u : 0u;
+#pragma unroll
+                for (int e = 0; e < V; ++e) v[e] = pick(pick(v[e], first, lm), last, rm);
+                stage[b][i * NTHR + tid] = v;
+            }
+        };
+        vec_t g[NCH];
+        fetch(z0 - R, g);
+        stash(0, g);
+        __syncthreads();
+        for (int t = 0; t < nt; ++t) {
+            const int b = t & 1;
+            if (t + 1 < nt) fetch(z0 - R + t + 1, g);
+            step(stage[b], z0 - R + t);
+            if (t + 1 < nt) stash(b ^ 1, g);
+            __syncthreads();
+        }
+    }
+}
+
+// FALLBACK: the launcher of the instance that takes what this kernel does not (rows that are not a
+// multiple of 16 bytes, unaligned base pointers, planes beyond 4 GiB).
+template <typename T, int P, int NW, int R, int NBUF, int NT, Launch3DFn FALLBACK>
+hipError_t launch3d_star(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
+{
+    constexpr int V = Piece16<T>::V;
+    const size_t slice = (size_t)(pr.march_y ? pr.D : pr.H) * (pr.march_y ? (size_t)pr.W * pr.H : (size_t)pr.W) * sizeof(T);
+    if (pr.W % V != 0 || slice > 0xffffffffull || (!dry_run && !pointers_aligned(pr.in, pr.out, 16)))
+        return FALLBACK(pr, tu, geo, dry_run);
+    Geometry g;
+    g.V = V;
+    g.P = P;
+    g.halo_left = g.halo_right = 0;
+    g.valid_lanes = kWave;
+    g.strips_x = ceil_div(pr.W, kWave * V);
+    g.rows_per_wave = P;
+    const int LH = pr.march_y ? pr.D : pr.H, LD = pr.march_y ? pr.H : pr.D;   // strip / march extents
+    g.tiles_y = ceil_div(LH, NW * P);
+    int planes = tu.planes_per_wave;
+    if (planes <= 0) {
+        // The longest z-chunks that still give every compute unit its share of blocks: each chunk
+        // re-reads 2R planes, and one round of equally long blocks finishes together (512^3, radius 4:
+        // fp32 202 -> 195 us from 64 to 128 planes, fp64 406 -> 364 us from 64 to 256).
+        int blocks_per_cu = 0, dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                &blocks_per_cu, reinterpret_cast<const void*>(&ssam3d_star_kernel<T, P, NW, R, NBUF, NT>), NW * kWave,
+                0) != hipSuccess || blocks_per_cu <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+            blocks_per_cu = 1;
+        }
+        planes = balanced_planes(LD, (long)g.strips_x * g.tiles_y, cus * blocks_per_cu, LD, 4 * R);
+    }
+    if (planes > LD) planes = LD;
+    g.planes_per_wave = planes;
+    g.tiles_z = ceil_div(LD, planes);
+    g.tiles = (long)g.strips_x * g.tiles_y * g.tiles_z;   // block tiles
+    g.xcd_remap = tu.xcd_remap < 0 ? 1 : (tu.xcd_remap ? 1 : 0);
+    g.blocks = g.tiles > kMaxBlocks ? -1 : (g.xcd_remap ? ceil_div((int)g.tiles, kXcds) * kXcds : (int)g.tiles);
+    if (geo) *geo = g;
+    if (!launchable(g)) return hipErrorInvalidConfiguration;
+    if (dry_run) return hipSuccess;
+
+    Args3D<T, 3 * (2 * R + 1)> a;
+    fill_args3d<T, V, R, R, R, 1>(pr, g, &a);
+    hipLaunchKernelGGL((ssam3d_star_kernel<T, P, NW, R, NBUF, NT>), dim3(g.blocks), dim3(NW * kWave), 0, pr.stream, a);
+    return hipGetLastError();
+}
+
+// FALLBACK is written as the launcher's template-id, e.g. (::ssam::launch3d_lds<float, 2, 4, 4, 4, 4, 4, 1, 2>).
+#define SSAM_INSTANCE_3D_STAR(T, DT, P, NW, R, NBUF, NT, FALLBACK, VARIANT)                             \
+    static ::ssam::Register3D SSAM_CAT(reg3ds_, __COUNTER__)(::ssam::Instance3D{                       \
+        #T "_r" #R #R #R "_b1_p" #P "w" #NW "star_ring" #NBUF "nt" #NT, DT, R, R, R, 1, VARIANT,        \
+        &::ssam::launch3d_star<T, P, NW, R, NBUF, NT, FALLBACK>})
+
+}  // namespace ssam

@@ -224,6 +224,46 @@ def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
             ssam.ssam_set_tuning(k, -1)
 
 
+STAR_SHAPES = [(33, 70, 260), (75, 9, 512), (10, 40, 4), (5, 3, 8), (13, 37, 132), (21, 66, 1028)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("r", [1, 2, 4])
+@pytest.mark.parametrize("tuning", [{}, {"variant": 10}, {"planes_per_wave": 5}, {"planes_per_wave": 8, "xcd_remap": 0},
+                                    {"march_axis": 1}, {"planes_per_wave": 1}, {"planes_per_wave": 2, "variant": 10},
+                                    {"march_axis": 1, "variant": 10, "planes_per_wave": 9}])
+def test_block_cooperative_star_kernel(ssam, dtype, r, tuning):
+    """3D stars on the block-cooperative kernel without halo lanes (rows that are a multiple of 16
+    bytes): both compiled tile shapes, short z-chunks, both march axes, both boundary rules, on grids
+    with partial strips, partial blocks in y, fewer planes than the radius and several strips."""
+    coef = wl.seeded_symmetric_star(r, 3, 640, dtype)
+    try:
+        for k, v in tuning.items():
+            ssam.ssam_set_tuning(k, v)
+        for k, shape in enumerate(STAR_SHAPES):
+            fld = wl.uniform_field(shape, -1.0, 1.0, 641 + k, dtype)
+            name = ssam.ssam_describe("stencil3d", shape, coef, "zero").split()[0]
+            assert "star_ring" in name, (name, tuning)
+            for bnd in ("zero", "clamp"):
+                print(f"star kernel {np.dtype(dtype).name} r{r} {tuning} {bnd} grid {shape} {name}", flush=True)
+                got = host(ssam.ssam_stencil3d(dev(fld), coef, bnd))
+                assert_parity(got, oracle.stencil(fld, coef, bnd), coef, 1.0, f"r{r} {tuning} {bnd} {shape}")
+        # unsymmetric coefficients: every tap multiplies its own neighbour
+        c2 = wl.seeded_coefficients(wl.mask_star(r, r, r), 650, dtype)
+        fld = wl.uniform_field((19, 41, 264), -1.0, 1.0, 651, dtype)
+        for bnd in ("zero", "clamp"):
+            got = host(ssam.ssam_stencil3d(dev(fld), c2, bnd))
+            assert_parity(got, oracle.stencil(fld, c2, bnd), c2, 1.0, f"r{r} {tuning} {bnd} unsymmetric")
+        # rows that are not a multiple of 16 bytes take the fallback instance
+        odd = wl.uniform_field((9, 12, 131), -1.0, 1.0, 652, dtype)
+        assert "halo_lanes=0+0" not in ssam.ssam_describe("stencil3d", odd.shape, coef, "zero")   # a tile plan with halo lanes
+        got = host(ssam.ssam_stencil3d(dev(odd), coef, "zero"))
+        assert_parity(got, oracle.stencil(odd, coef, "zero"), coef, 1.0, f"r{r} {tuning} fallback")
+    finally:
+        for k in tuning:
+            ssam.ssam_set_tuning(k, -1)
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_iterate_matches_oracle_and_ping_pongs(ssam, dtype):
     cases = [((70, 300), wl.seeded_coefficients(wl.mask_box(2, 2), 801, dtype)[0]),
