@@ -2,14 +2,8 @@
 #include "ssam_kernel2d_fused.h"
 
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 3, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 1, 3, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 4, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 1, 4, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 2, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 2, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 2, 3, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 2, 3, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 1, 2, 4, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 1, 2, 4, 2, 1);

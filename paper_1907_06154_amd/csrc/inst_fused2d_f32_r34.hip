@@ -2,9 +2,7 @@
 #include "ssam_kernel2d_fused.h"
 
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 3, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 3, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 3, 1, 3, 2, 0);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 3, 1, 4, 2, 0);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 4, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 8, 4, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(float, SSAM_F32, 4, 4, 4, 1, 3, 2, 0);

@@ -2,10 +2,8 @@
 #include "ssam_kernel2d_fused.h"
 
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 8, 2, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 1, 3, 2, 0);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 1, 4, 2, 0);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 2, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 8, 2, 2, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 2, 3, 2, 0);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 2, 2, 4, 2, 0);

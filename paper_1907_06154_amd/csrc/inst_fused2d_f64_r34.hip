@@ -2,8 +2,6 @@
 #include "ssam_kernel2d_fused.h"
 
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 3, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 8, 3, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 3, 1, 3, 2, 0);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 4, 1, 2, 2, 0);
-SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 8, 4, 1, 2, 2, 1);
 SSAM_INSTANCE_2D_FUSED(double, SSAM_F64, 2, 4, 4, 1, 3, 2, 0);

@@ -3,6 +3,4 @@
 #include "ssam_kernel3d_fused.h"
 
 SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 1, 0, 2, 0);
-SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 1, 1, 2, 1);
 SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 2, 0, 2, 0);
-SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 2, 1, 2, 1);

@@ -3,8 +3,5 @@
 #include "ssam_kernel3d_fused.h"
 
 SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 1, 2, 0);
-SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 1, 0, 2, 1);
 SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 2, 0, 2, 0);
-SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 2, 1, 2, 1);
 SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 3, 1, 2, 0);
-SSAM_INSTANCE_3D_FUSED(double, SSAM_F64, 2, 4, 1, 1, 1, 3, 0, 2, 1);

@@ -4,4 +4,3 @@
 #include "ssam_kernel3d_fused.h"
 
 SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 2, 4, 2, 2, 2, 1, 1, 2, 0);
-SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 2, 4, 2, 2, 2, 1, 0, 2, 1);

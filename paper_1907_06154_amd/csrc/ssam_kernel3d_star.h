@@ -99,9 +99,9 @@ __device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base)
 // Sixteen zero bytes: what a piece outside the grid is loaded from under zero padding.
 static __device__ __align__(16) const unsigned kZeroPiece[4] = {0u, 0u, 0u, 0u};
 
-template <typename T, int P, int NW, int R, int NBUF, int NT>
+template <typename T, int P, int NW, int R, int BUDGET, int NBUF, int NT>
 __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) void ssam3d_star_kernel(
-    const Args3D<T, 3 * (2 * R + 1)> a)
+    const Args3D<T, SliceMask<R, R, R, BUDGET, 0>::kNW> a)
 {
     static_assert(NBUF == 3 || NBUF == 4, "a ring of three or four staged planes");
     constexpr int PF = NBUF - 1;               // planes requested ahead
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     constexpr int NCH = (TOTAL + NTHR - 1) / NTHR;   // pieces one thread fetches per plane
     constexpr int SLOTS = NCH * NTHR;          // LDS pieces per buffer (the last few are padding)
     constexpr bool NT_STORE = (NT & kStreamStores) != 0;
-    static_assert((PF - 1) * (NCH + P) <= 30, "request count beyond what the wait encodes");
+    static_assert((PF - 1) * NCH + PF * P <= 30, "request count beyond what the wait encodes");
 
     __shared__ vec_t stage[NBUF][SLOTS];
 
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int z1 = min(z0 + a.planes_per_wave, D);
     const bool clamp = a.boundary == kClamp;
     const T* __restrict__ in = a.in;
-    typedef Args3D<T, 3 * NZ> Args;
-    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));   // z line (centre at R), y line, x line
+    typedef Args3D<T, SliceMask<R, R, R, BUDGET, 0>::kNW> Args;
+    const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));   // star: z line (centre at R), y line, x line; else dense [dz][dx][dy]
     const size_t rowst = (size_t)a.stride_row, plane = (size_t)a.stride_plane;
     const int nt = (z1 - z0) + 2 * R;          // input planes z0-R .. z1-1+R
 
@@ -179,66 +179,126 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 
     // one step of the march: the staged plane `st` is input plane zin
     auto step = [&](const vec_t* st, int zin) __attribute__((always_inline)) {
-        T sum[P][V];       // in-plane sums, seeded with the plane above's partial sums
-        // -- per window: z taps and the centre tap (in-flight plane s takes dz = R - s from this
-        //    input plane), then the x taps: neighbouring columns of the centre row, shifted in
-        //    from the lanes beside (the columns beyond the wave's own come in as the edge lanes'
-        //    "old" values)
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            T xs[(2 * HC + 1) * V];     // columns -HC*V .. (HC+1)*V - 1 relative to the lane's first
-            const vec_t v = st[own + (p + R) * RS];
-#pragma unroll
-            for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
-            const T* cen = &xs[HC * V];
-#pragma unroll
-            for (int s = 0; s < R; ++s)
-#pragma unroll
-                for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
-#pragma unroll
-            for (int j = 0; j < V; ++j) sum[p][j] = fma_into(cen[j], wts[R], acc[R + 1][p][j]);
-#pragma unroll
-            for (int s = R + 1; s < NZ - 1; ++s)
-#pragma unroll
-                for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[NZ - 1][p][j] = cen[j] * wts[0];
-#pragma unroll
-            for (int h = 1; h <= HC; ++h) {
-                const vec_t el = st[edge_l + (p + R) * RS + (HC - h)];   // same address in every lane: a broadcast
-                const vec_t er = st[edge_r + (p + R) * RS + (h - 1)];
-#pragma unroll
-                for (int j = 0; j < V; ++j) {
-                    xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
-                    xs[(HC + h) * V + j] = shift_in_down(xs[(HC + h - 1) * V + j], (T)er[j]);
-                }
-            }
-#pragma unroll
-            for (int dx = -R; dx <= R; ++dx) {
-                if (dx == 0) continue;
-                const T wx = wts[2 * NZ + dx + R];
-#pragma unroll
-                for (int j = 0; j < V; ++j) sum[p][j] = fma_t(xs[HC * V + j + dx], wx, sum[p][j]);
-            }
-        }
-        // -- y taps: every staged row of the wave's window
-#pragma unroll
-        for (int k = 0; k < C; ++k) {
-            const vec_t v = st[own + k * RS];
+        if constexpr (BUDGET == 1) {
+            T sum[P][V];       // in-plane sums, seeded with the plane above's partial sums
+            // -- per window: z taps and the centre tap (in-flight plane s takes dz = R - s from this
+            //    input plane), then the x taps: neighbouring columns of the centre row, shifted in
+            //    from the lanes beside (the columns beyond the wave's own come in as the edge lanes'
+            //    "old" values)
 #pragma unroll
             for (int p = 0; p < P; ++p) {
-                const int dy = k - R - p;
-                if (dy != 0 && dy >= -R && dy <= R) {
-                    const T wy = wts[NZ + dy + R];
+                T xs[(2 * HC + 1) * V];     // columns -HC*V .. (HC+1)*V - 1 relative to the lane's first
+                const vec_t v = st[own + (p + R) * RS];
 #pragma unroll
-                    for (int j = 0; j < V; ++j) sum[p][j] = fma_t((T)v[j], wy, sum[p][j]);
+                for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
+                const T* cen = &xs[HC * V];
+#pragma unroll
+                for (int s = 0; s < R; ++s)
+#pragma unroll
+                    for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
+#pragma unroll
+                for (int j = 0; j < V; ++j) sum[p][j] = fma_into(cen[j], wts[R], acc[R + 1][p][j]);
+#pragma unroll
+                for (int s = R + 1; s < NZ - 1; ++s)
+#pragma unroll
+                    for (int j = 0; j < V; ++j) acc[s][p][j] = fma_into(cen[j], wts[2 * R - s], acc[s + 1][p][j]);
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[NZ - 1][p][j] = cen[j] * wts[0];
+#pragma unroll
+                for (int h = 1; h <= HC; ++h) {
+                    const vec_t el = st[edge_l + (p + R) * RS + (HC - h)];   // same address in every lane: a broadcast
+                    const vec_t er = st[edge_r + (p + R) * RS + (h - 1)];
+#pragma unroll
+                    for (int j = 0; j < V; ++j) {
+                        xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
+                        xs[(HC + h) * V + j] = shift_in_down(xs[(HC + h - 1) * V + j], (T)er[j]);
+                    }
+                }
+#pragma unroll
+                for (int dx = -R; dx <= R; ++dx) {
+                    if (dx == 0) continue;
+                    const T wx = wts[2 * NZ + dx + R];
+#pragma unroll
+                    for (int j = 0; j < V; ++j) sum[p][j] = fma_t(xs[HC * V + j + dx], wx, sum[p][j]);
                 }
             }
+            // -- y taps: every staged row of the wave's window
+#pragma unroll
+            for (int k = 0; k < C; ++k) {
+                const vec_t v = st[own + k * RS];
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const int dy = k - R - p;
+                    if (dy != 0 && dy >= -R && dy <= R) {
+                        const T wy = wts[NZ + dy + R];
+#pragma unroll
+                        for (int j = 0; j < V; ++j) sum[p][j] = fma_t((T)v[j], wy, sum[p][j]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int j = 0; j < V; ++j) acc[R][p][j] = sum[p][j];
+        } else {
+            // Any tap shape (BUDGET 2: faces and edges, 3: the dense box): row by row, every staged row
+            // of the window extended by the neighbouring columns it needs, shifted in from the lanes
+            // beside; row k holds the taps dy = k - R - p of window p, for every in-flight plane s
+            // (dz = R - s).  The first product a sum receives starts it from the partial sum of the
+            // plane above (slot s + 1), so the planes advance one slot per step as in the star.
+            T nacc[NZ][P][V];
+            bool have[NZ][P];
+#pragma unroll
+            for (int s = 0; s < NZ; ++s)
+#pragma unroll
+                for (int p = 0; p < P; ++p) have[s][p] = false;
+#pragma unroll
+            for (int k = 0; k < C; ++k) {
+                T xs[(2 * HC + 1) * V];
+                const vec_t v = st[own + k * RS];
+#pragma unroll
+                for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
+#pragma unroll
+                for (int h = 1; h <= HC; ++h) {
+                    const vec_t el = st[edge_l + k * RS + (HC - h)];
+                    const vec_t er = st[edge_r + k * RS + (h - 1)];
+#pragma unroll
+                    for (int j = 0; j < V; ++j) {
+                        xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
+                        xs[(HC + h) * V + j] = shift_in_down(xs[(HC + h - 1) * V + j], (T)er[j]);
+                    }
+                }
+                static_for<NZ>([&](auto sc) __attribute__((always_inline)) {
+                    constexpr int sl = decltype(sc)::value;
+                    typedef SliceMask<R, R, R, BUDGET, R - sl> Mask;
+#pragma unroll
+                    for (int p = 0; p < P; ++p) {
+                        const int n = k - p;                 // dy + R
+                        if (n < 0 || n > 2 * R) continue;
+#pragma unroll
+                        for (int m = 0; m < 2 * R + 1; ++m) {
+                            if (!Mask::tap(n, m)) continue;
+                            const T w = wts[Mask::widx(n, m)];
+#pragma unroll
+                            for (int j = 0; j < V; ++j) {
+                                const T x = xs[HC * V + j + m - R];
+                                if (have[sl][p]) nacc[sl][p][j] = fma_t(x, w, nacc[sl][p][j]);
+                                else if (sl < NZ - 1) nacc[sl][p][j] = fma_into(x, w, acc[sl < NZ - 1 ? sl + 1 : sl][p][j]);
+                                else nacc[sl][p][j] = x * w;
+                            }
+                            have[sl][p] = true;
+                        }
+                    }
+                });
+            }
+#pragma unroll
+            for (int s = 0; s < NZ; ++s)
+#pragma unroll
+                for (int p = 0; p < P; ++p)
+#pragma unroll
+                    for (int j = 0; j < V; ++j)
+                        acc[s][p][j] = have[s][p] ? nacc[s][p][j] : (s < NZ - 1 ? acc[s < NZ - 1 ? s + 1 : s][p][j] : T(0));
         }
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-#pragma unroll
-            for (int j = 0; j < V; ++j) acc[R][p][j] = sum[p][j];
 
         // output plane zin - R has now received its last contribution
         const int zo = zin - R;
@@ -271,18 +331,18 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             if (k < nt) request(z0 - R + k, k);
         int b = 0;
         for (int t = 0; t < nt; ++t) {
-            // Requests younger than those of plane t, counting only what is certainly younger: the
-            // loads of planes t+1 .. t+PF-1 (issued in steps t-PF+1 .. t-1) and the stores of steps
-            // t-PF+1 .. t-1.
+            // Requests younger than those of plane t (issued at the start of step t - PF): the stores of
+            // steps t-PF .. t-1 and the loads of planes t+1 .. t+PF-1 (issued in steps t-PF+1 .. t-1).
             int younger = 0;
 #pragma unroll
-            for (int k = 1; k < PF; ++k) {
-                if (t + k < nt) younger += NCH;
+            for (int k = 1; k <= PF; ++k) {
+                if (k < PF && t + k < nt) younger += NCH;
                 if (full_rows && t - k >= 2 * R) younger += P;
             }
             wait_and_sync(younger);
             // buffer (t + PF) % NBUF held plane t - 1, which every wave has finished reading
             if (t + PF < nt) request(z0 - R + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
+            asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it
             step(stage[b], z0 - R + t);
             b = b + 1 == NBUF ? 0 : b + 1;
         }
@@ -320,7 +380,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 
 // FALLBACK: the launcher of the instance that takes what this kernel does not (rows that are not a
 // multiple of 16 bytes, unaligned base pointers, planes beyond 4 GiB).
-template <typename T, int P, int NW, int R, int NBUF, int NT, Launch3DFn FALLBACK>
+template <typename T, int P, int NW, int R, int BUDGET, int NBUF, int NT, Launch3DFn FALLBACK>
 hipError_t launch3d_star(const Problem3D& pr, const Tuning& tu, Geometry* geo, bool dry_run)
 {
     constexpr int V = Piece16<T>::V;
@@ -345,7 +405,7 @@ hipError_t launch3d_star(const Problem3D& pr, const Tuning& tu, Geometry* geo, b
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &blocks_per_cu, reinterpret_cast<const void*>(&ssam3d_star_kernel<T, P, NW, R, NBUF, NT>), NW * kWave,
+                &blocks_per_cu, reinterpret_cast<const void*>(&ssam3d_star_kernel<T, P, NW, R, BUDGET, NBUF, NT>), NW * kWave,
                 0) != hipSuccess || blocks_per_cu <= 0) {
             (void)hipGetLastError();
             cus = 256;
@@ -363,16 +423,18 @@ hipError_t launch3d_star(const Problem3D& pr, const Tuning& tu, Geometry* geo, b
     if (!launchable(g)) return hipErrorInvalidConfiguration;
     if (dry_run) return hipSuccess;
 
-    Args3D<T, 3 * (2 * R + 1)> a;
-    fill_args3d<T, V, R, R, R, 1>(pr, g, &a);
-    hipLaunchKernelGGL((ssam3d_star_kernel<T, P, NW, R, NBUF, NT>), dim3(g.blocks), dim3(NW * kWave), 0, pr.stream, a);
+    Args3D<T, SliceMask<R, R, R, BUDGET, 0>::kNW> a;
+    fill_args3d<T, V, R, R, R, BUDGET>(pr, g, &a);
+    hipLaunchKernelGGL((ssam3d_star_kernel<T, P, NW, R, BUDGET, NBUF, NT>), dim3(g.blocks), dim3(NW * kWave), 0, pr.stream, a);
     return hipGetLastError();
 }
 
 // FALLBACK is written as the launcher's template-id, e.g. (::ssam::launch3d_lds<float, 2, 4, 4, 4, 4, 4, 1, 2>).
-#define SSAM_INSTANCE_3D_STAR(T, DT, P, NW, R, NBUF, NT, FALLBACK, VARIANT)                             \
+#define SSAM_INSTANCE_3D_RING(T, DT, P, NW, R, BUDGET, NBUF, NT, FALLBACK, VARIANT)                     \
     static ::ssam::Register3D SSAM_CAT(reg3ds_, __COUNTER__)(::ssam::Instance3D{                       \
-        #T "_r" #R #R #R "_b1_p" #P "w" #NW "star_ring" #NBUF "nt" #NT, DT, R, R, R, 1, VARIANT,        \
-        &::ssam::launch3d_star<T, P, NW, R, NBUF, NT, FALLBACK>})
+        #T "_r" #R #R #R "_b" #BUDGET "_p" #P "w" #NW "star_ring" #NBUF "nt" #NT, DT, R, R, R, BUDGET,  \
+        VARIANT, &::ssam::launch3d_star<T, P, NW, R, BUDGET, NBUF, NT, FALLBACK>})
+#define SSAM_INSTANCE_3D_STAR(T, DT, P, NW, R, NBUF, NT, FALLBACK, VARIANT)                             \
+    SSAM_INSTANCE_3D_RING(T, DT, P, NW, R, 1, NBUF, NT, FALLBACK, VARIANT)
 
 }  // namespace ssam

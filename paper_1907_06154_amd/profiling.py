@@ -1,0 +1,269 @@
+"""Turns rocprofv3 output into the short summaries kept under profiles/ (text only), and keeps
+profiles/measured_traffic.json, the HBM bytes per launch that bench.py reports as roofline.traffic.
+
+    python -m paper_1907_06154_amd.profiling summarize <prefix> <out.md> --title T --bench-args "..."
+    python -m paper_1907_06154_amd.profiling sq <counter dir> [<counter dir> ...] <out.md>
+    python -m paper_1907_06154_amd.profiling lds <counter dir> [<counter dir> ...] <out.md>
+    python -m paper_1907_06154_amd.profiling resources <out.md>
+
+`summarize` expects three rocprofv3 runs of the same bench.py command (the commands are written
+into the summary), each with its bench.py output saved beside it:
+    <prefix>_trace/  (--kernel-trace --stats)   <prefix>_trace.json
+    <prefix>_fetch/  (--pmc FETCH_SIZE)         <prefix>_fetch.json
+    <prefix>_write/  (--pmc WRITE_SIZE)         <prefix>_write.json
+The counters are scaled by what they read for the plain copy kernel of known size that bench.py
+runs first (ssam_probe_copy).  Dispatches are matched to kernel instances by their order: the
+counter runs use --steps 1 --warmup 0, so the library's dispatches are exactly the launches
+bench.py lists per case ("launch_names").
+
+`resources` compiles every translation unit for gfx950 with -Rpass-analysis=kernel-resource-usage
+(no GPU needed) and tabulates registers, LDS, scratch and waves per SIMD of every kernel.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import glob
+import json
+import os
+import re
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+TRAFFIC = os.path.join(ROOT, "profiles", "measured_traffic.json")
+
+
+def short(name: str) -> str:
+    name = name.replace("void ssam::", "").replace("ssam::(anonymous namespace)::", "")
+    return name.split("(ssam::")[0].split("(HIP_vector")[0].split("(float")[0].split("(double")[0]
+
+
+def ours(kernel: str) -> bool:
+    """A compute kernel of the library (not its plain copy kernel, not one of torch's)."""
+    k = short(kernel)
+    return k.startswith(("ssam2d", "ssam3d", "scan_", "generic_kernel"))
+
+
+def is_copy(kernel: str) -> bool:
+    return short(kernel).startswith("copy_kernel")
+
+
+def one(pattern: str) -> str:
+    hits = glob.glob(pattern, recursive=True)
+    if not hits:
+        raise SystemExit(f"nothing matches {pattern}")
+    return hits[0]
+
+
+def load_traffic() -> dict:
+    try:
+        return json.load(open(TRAFFIC))
+    except (OSError, ValueError):
+        return {"comment": "HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the readings of the "
+                           "plain copy kernel; keys: <kernel instance>@<grid>; written by paper_1907_06154_amd.profiling",
+                "bytes_per_launch": {}, "source": {}}
+
+
+def counter_dispatches(dirname: str):
+    """[(kernel, {counter: value}, duration_us)] in dispatch order."""
+    rows = collections.OrderedDict()
+    for r in csv.DictReader(open(one(os.path.join(dirname, "**", "*counter_collection.csv")))):
+        d = rows.setdefault(int(r["Dispatch_Id"]), {"kernel": short(r["Kernel_Name"]), "c": {},
+                                                    "us": (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3})
+        d["c"][r["Counter_Name"]] = d["c"].get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+    return [(d["kernel"], d["c"], d["us"]) for _, d in sorted(rows.items())]
+
+
+def summarize(prefix: str, out_md: str, title: str, bench_args: str) -> None:
+    bench = {k: json.load(open(f"{prefix}_{k}.json")) for k in ("trace", "fetch", "write")}
+    out = [f"# rocprofv3 summary: {title}\n"]
+    cmd = f"python3 bench.py {bench_args} --no-cpu-baseline"
+    out.append(f"Kernel durations:\n\n    rocprofv3 --kernel-trace --stats --output-format csv -d {prefix}_trace -o c -- {cmd} "
+               f"--steps {bench['trace']['steps']} --warmup {bench['trace']['warmup']}\n")
+    out.append("| kernel | calls | avg us | min us | max us | % of GPU time |\n|---|---|---|---|---|---|")
+    for r in csv.DictReader(open(one(os.path.join(prefix + "_trace", "**", "*kernel_stats.csv")))):
+        if ours(r["Name"]) or is_copy(r["Name"]):
+            out.append(f"| `{short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | {float(r['MinNs']) / 1e3:.1f} | "
+                       f"{float(r['MaxNs']) / 1e3:.1f} | {r['Percentage']} |")
+    b = bench["trace"]
+    out.append("\nThe same run's bench.py line (HIP events on the launch stream, median over the steps; a launch of a `_fusedS` "
+               "instance performs S sweeps, so GStencil/s counts S updates per point per launch while the algorithmic GB/s is "
+               "the one read and one write the launch makes):\n")
+    out.append("| case | kernel instance (most launches) | launches per step | launch us | GStencil/s | algorithmic GB/s per launch "
+               "| fraction of 8 TB/s | TFLOP/s | fraction of published vector peak |\n|---|---|---|---|---|---|---|---|---|")
+    for k in b["kernels"]:
+        out.append(f"| {k['case']} | `{k['kernel']}` | {k['launches_per_step']} | {k['launch_ms'] * 1e3:.1f} | {k['gstencil_per_s']:.1f} | "
+                   f"{k['hbm_GBps']:.0f} | {k['hbm_frac']:.3f} | {k['alu_TFLOPs']:.1f} | {k['alu_frac']:.3f} |")
+    out.append(f"\nWhole bench line: value {b['value']:.1f} {b['unit']}, {b['ms_per_step']:.2f} ms per step "
+               f"({len(b['kernels'])} cases, timed region {b['consistency']['timed_region_s']:.2f} s).\n")
+
+    out.append("HBM traffic counters (each in a run of its own; per dispatch, mean over the dispatches of an instance):\n")
+    for kind, ctr in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+        out.append(f"    rocprofv3 --pmc {ctr} --kernel-trace --output-format csv -d {prefix}_{kind} -o c -- {cmd} --steps 1 --warmup 0")
+    out.append("")
+    per_inst = {}
+    scale = {}
+    grid = b["config"]["grid"]
+    for kind, ctr in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+        disp = counter_dispatches(f"{prefix}_{kind}")
+        names = [n for k in bench[kind]["kernels"] for n in k["launch_names"]]
+        mine = [(k, c) for k, c, _ in disp if ours(k)]
+        if len(mine) != len(names):
+            raise SystemExit(f"{prefix}_{kind}: {len(mine)} library dispatches for {len(names)} launches bench.py lists")
+        copies = [c[ctr] for k, c, _ in disp if is_copy(k)]
+        copy_bytes = bench[kind]["copy_bytes_each_way"]
+        scale[kind] = (copy_bytes / 1024.0) / (sum(copies) / len(copies))
+        for inst, (k, c) in zip(names, mine):
+            per_inst.setdefault(inst, {"kernel": k, "fetch": [], "write": []})[kind].append(c[ctr])
+    out.append(f"The plain copy kernel (`ssam_probe_copy`, {bench['fetch']['copy_bytes_each_way'] / 2 ** 20:.0f} MiB read and written) "
+               f"gives the scale factors {scale['fetch']:.3f} (FETCH_SIZE, KiB) and {scale['write']:.3f} (WRITE_SIZE, KiB).\n")
+    out.append("| kernel instance | kernel | dispatches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled read MiB | scaled write MiB | "
+               "algorithmic MiB per launch (read+write) | traffic / algorithmic |\n|---|---|---|---|---|---|---|---|---|")
+    traffic = load_traffic()
+    esz = {"float": 4, "double": 8}
+    pts = 1
+    for s in grid.split("x"):
+        pts *= int(s)
+    for inst, v in per_inst.items():
+        f = sum(v["fetch"]) / len(v["fetch"])
+        w = sum(v["write"]) / len(v["write"])
+        alg = 2 * pts * esz[inst.split("_")[0]] / 2 ** 20
+        tot = (f * scale["fetch"] + w * scale["write"]) / 1024
+        out.append(f"| `{inst}` | `{v['kernel']}` | {len(v['fetch'])} | {f:.0f} | {w:.0f} | {f * scale['fetch'] / 1024:.1f} | "
+                   f"{w * scale['write'] / 1024:.1f} | {alg:.0f} | {tot / alg:.3f} |")
+        traffic["bytes_per_launch"][f"{inst}@{grid}"] = int(tot * 2 ** 20)
+        traffic["source"][f"{inst}@{grid}"] = os.path.relpath(out_md, ROOT)
+    open(out_md, "w").write("\n".join(out) + "\n")
+    json.dump(traffic, open(TRAFFIC, "w"), indent=1, sort_keys=True)
+    print("\n".join(out))
+
+
+def sweeps_of(kernel: str) -> int:
+    if "ssam2d_fused" in kernel:
+        return int(re.search(r">, (\d+), \d+>$", kernel).group(1))
+    return 2 if "ssam3d_fused" in kernel else 1
+
+
+def sq(dirs, out_md: str) -> None:
+    """VALU utilisation per kernel from one pass of 8 SQ counters per directory."""
+    ctrs = "SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS SQ_INSTS_VALU SQ_INSTS_LDS SQ_WAIT_ANY"
+    out = ["# VALU utilisation of the benchmark kernels (rocprofv3 SQ counters)\n",
+           "One MI355X, one counter pass per configuration (8 SQ counters):\n",
+           f"    rocprofv3 --pmc {ctrs} --kernel-trace --output-format csv -d <dir> -o c -- python3 bench.py --workload config<N> "
+           "--no-cpu-baseline --steps 1 --warmup 0\n",
+           "Per dispatch, mean over the dispatches of a kernel.  `VALU instr / point / sweep` = SQ_INSTS_VALU x 64 lanes / (grid "
+           "points x sweeps of the launch): what one output costs in lane-instructions, halo lanes and warm-up rows included.  "
+           "`VALU busy` = (SQ_ACTIVE_INST_VALU + SQ_INSTS_MFMA) x 4 cycles / (1024 SIMDs x dispatch duration x 2.4 GHz): the "
+           "fraction of all VALU issue slots of the chip the kernel used.  `MFMA share` = SQ_INSTS_MFMA / SQ_INSTS_VALU.  "
+           "`waiting` = SQ_WAIT_ANY / SQ_WAVE_CYCLES: share of wave-cycles spent waiting on any counter (memory, LDS).  "
+           "Durations are those of the counter run (serialised dispatches), a few per cent above the timed runs.\n",
+           "| run | kernel | dispatches | duration us | sweeps | VALU instr / point / sweep | VALU busy | MFMA share | "
+           "LDS instr / VALU instr | waiting |\n|---|---|---|---|---|---|---|---|---|---|"]
+    for d in dirs:
+        bench = json.load(open(d.rstrip("/") + ".json"))
+        pts = 1
+        for s in bench["config"]["grid"].split("x"):
+            pts *= int(s)
+        agg = collections.OrderedDict()
+        for k, c, us in counter_dispatches(d):
+            if ours(k):
+                agg.setdefault(k, []).append((c, us))
+        for k, rows in agg.items():
+            m = {name: sum(r[0].get(name, 0.0) for r in rows) / len(rows) for name in ctrs.split()}
+            us = sum(r[1] for r in rows) / len(rows)
+            sw = sweeps_of(k)
+            out.append(f"| {os.path.basename(d.rstrip('/'))} | `{k}` | {len(rows)} | {us:.1f} | {sw} | "
+                       f"{m['SQ_INSTS_VALU'] * 64 / pts / sw:.1f} | "
+                       f"{(m['SQ_ACTIVE_INST_VALU'] + m['SQ_INSTS_MFMA']) * 4 / (1024 * us * 1e-6 * 2.4e9):.2f} | "
+                       f"{m['SQ_INSTS_MFMA'] / max(m['SQ_INSTS_VALU'], 1):.2f} | {m['SQ_INSTS_LDS'] / max(m['SQ_INSTS_VALU'], 1):.3f} | "
+                       f"{m['SQ_WAIT_ANY'] / max(m['SQ_WAVE_CYCLES'], 1):.2f} |")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
+def lds(dirs, out_md: str) -> None:
+    """LDS bank conflicts of the kernels that use LDS."""
+    ctrs = "SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_LDS_ADDR_CONFLICT SQ_INSTS_LDS SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_WAIT_INST_LDS"
+    out = ["# LDS bank conflicts of the kernels that use LDS (rocprofv3 SQ counters)\n",
+           "One MI355X, one counter pass per configuration:\n",
+           f"    rocprofv3 --pmc {ctrs} --kernel-trace --output-format csv -d <dir> -o c -- python3 bench.py --workload config<N> "
+           "--no-cpu-baseline --steps 1 --warmup 0\n",
+           "Per dispatch, mean over the dispatches of a kernel.  `conflict share` = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE: "
+           "cycles the LDS spent replaying bank conflicts over the cycles it was busy with indexed accesses.  `LDS busy` = "
+           "SQ_LDS_IDX_ACTIVE / (256 CUs x dispatch duration x 2.4 GHz).  Kernels that issue no LDS instruction are left out.\n",
+           "| run | kernel | dispatches | duration us | LDS instructions | conflict cycles | LDS active cycles | conflict share | LDS busy |\n"
+           "|---|---|---|---|---|---|---|---|---|"]
+    for d in dirs:
+        agg = collections.OrderedDict()
+        for k, c, us in counter_dispatches(d):
+            if ours(k):
+                agg.setdefault(k, []).append((c, us))
+        for k, rows in agg.items():
+            m = {name: sum(r[0].get(name, 0.0) for r in rows) / len(rows) for name in ctrs.split()}
+            if m["SQ_INSTS_LDS"] == 0:
+                continue
+            us = sum(r[1] for r in rows) / len(rows)
+            out.append(f"| {os.path.basename(d.rstrip('/'))} | `{k}` | {len(rows)} | {us:.1f} | {m['SQ_INSTS_LDS']:.0f} | "
+                       f"{m['SQ_LDS_BANK_CONFLICT']:.0f} | {m['SQ_LDS_IDX_ACTIVE']:.0f} | "
+                       f"{m['SQ_LDS_BANK_CONFLICT'] / max(m['SQ_LDS_IDX_ACTIVE'], 1):.3f} | "
+                       f"{m['SQ_LDS_IDX_ACTIVE'] / (256 * us * 1e-6 * 2.4e9):.2f} |")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
+def resources(out_md: str, only_default: bool = True) -> None:
+    from . import build
+    flags = [f for f in build.FLAGS if f not in ("-fPIC",)]
+    rows = []
+    for src in sorted(glob.glob(os.path.join(build.CSRC, "*.hip"))):
+        res = subprocess.run(["hipcc", *flags, "--cuda-device-only", "-c", src, "-o", "/dev/null",
+                              "-Rpass-analysis=kernel-resource-usage"], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise SystemExit(res.stderr)
+        cur = None
+        for line in res.stderr.splitlines():
+            m = re.search(r"remark: [^ ]+ (Function Name|VGPRs|AGPRs|SGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|LDS Size \[bytes/block\]): (\S+)", line)
+            if not m:
+                continue
+            if m.group(1) == "Function Name":
+                name = subprocess.run(["c++filt", m.group(2)], capture_output=True, text=True).stdout.strip()
+                cur = {"file": os.path.basename(src), "kernel": short(name)}
+                rows.append(cur)
+            elif cur is not None:
+                cur[m.group(1).split(" [")[0]] = m.group(2)
+    out = ["# Registers, LDS and scratch of every compiled kernel (gfx950)\n",
+           "From the compiler's resource report, no GPU involved:\n",
+           "    python -m paper_1907_06154_amd.profiling resources profiles/kernel_resources.md\n",
+           "(`hipcc --offload-arch=gfx950 -O3 ... --cuda-device-only -Rpass-analysis=kernel-resource-usage` per translation unit.)  "
+           "VGPRs + AGPRs share one file of 512 registers per SIMD lane: waves per SIMD = floor(512 / (VGPRs + AGPRs, rounded up "
+           "to 8)), at most 8; a block's LDS also limits the blocks per compute unit (160 KiB).  Scratch is 0 for every kernel a "
+           "default dispatch uses.\n",
+           "| translation unit | kernel | VGPRs | AGPRs | SGPRs | LDS bytes / block | scratch bytes / lane | waves / SIMD |\n|---|---|---|---|---|---|---|---|"]
+    for r in rows:
+        out.append(f"| {r['file']} | `{r['kernel']}` | {r.get('VGPRs', '')} | {r.get('AGPRs', '')} | {r.get('SGPRs', '')} | "
+                   f"{r.get('LDS Size', '')} | {r.get('ScratchSize', '')} | {r.get('Occupancy', '')} |")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print(f"{len(rows)} kernels -> {out_md}")
+
+
+def main(argv) -> int:
+    if len(argv) >= 3 and argv[0] == "summarize":
+        title = argv[argv.index("--title") + 1]
+        bargs = argv[argv.index("--bench-args") + 1]
+        summarize(argv[1], argv[2], title, bargs)
+    elif len(argv) >= 3 and argv[0] == "sq":
+        sq(argv[1:-1], argv[-1])
+    elif len(argv) >= 3 and argv[0] == "lds":
+        lds(argv[1:-1], argv[-1])
+    elif len(argv) == 2 and argv[0] == "resources":
+        resources(argv[1])
+    else:
+        print(__doc__)
+        return 2
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 
 import oracle  # noqa: E402
-from paper_1907_06154_amd import workloads as wl  # noqa: E402
+import workloads as wl  # noqa: E402
 
 
 def cases():

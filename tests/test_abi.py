@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import paper_1907_06154_amd as ssam
-from paper_1907_06154_amd import workloads as wl
+import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE_A, FAKE_B = 0x10000000, 0x50000000      # never dereferenced: validation fails first

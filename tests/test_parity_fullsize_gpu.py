@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_1907_06154_amd import workloads as wl
+import workloads as wl
 from parity_util import assert_parity, oracle_window
 
 pytestmark = pytest.mark.gpu

@@ -7,7 +7,7 @@ the interior) on crops regenerated from the same counters.  Same tolerance as ev
 import numpy as np
 import pytest
 
-from paper_1907_06154_amd import workloads as wl
+import workloads as wl
 from parity_util import assert_parity, oracle_window
 
 pytestmark = pytest.mark.gpu

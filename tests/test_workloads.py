@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from paper_1907_06154_amd import workloads as wl
+import workloads as wl
 
 
 def test_splitmix64_known_sequence():

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_1907_06154_amd import workloads as wl
+import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
