@@ -76,6 +76,22 @@ def conv2d(image: np.ndarray, filt: np.ndarray, boundary: str = "clamp",
     return out
 
 
+def conv3d(volume: np.ndarray, filt: np.ndarray, boundary: str = "clamp",
+           anchor: Optional[Tuple[int, int, int]] = None) -> np.ndarray:
+    """volume [D][H][W]; filt [K][N][M]; anchor (ax, ay, az), default (M//2, N//2, K//2)."""
+    volume = np.ascontiguousarray(volume)
+    filt = np.ascontiguousarray(filt, dtype=volume.dtype)
+    D, H, W = volume.shape
+    K, N, M = filt.shape
+    ax, ay, az = (M // 2, N // 2, K // 2) if anchor is None else anchor
+    out = np.empty_like(volume)
+    fn = getattr(_load(), "oracle_conv3d_" + _suffix(volume.dtype))
+    rc = fn(_ptr(volume), _ptr(out), W, H, D, _ptr(filt), M, N, K, int(ax), int(ay), int(az), BOUNDARY[boundary])
+    if rc != 0:
+        raise ValueError("oracle_conv3d rejected its arguments")
+    return out
+
+
 def _box_radii(coef: np.ndarray) -> Tuple[int, int, int]:
     if coef.ndim == 2:
         coef = coef[None]

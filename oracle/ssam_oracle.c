@@ -1,4 +1,4 @@
-/* CPU oracle for structured-grid weighted sums (2D filter, 2D/3D stencil, Jacobi iteration).
+/* CPU oracle for structured-grid weighted sums (2D and 3D filter, 2D/3D stencil, Jacobi iteration, scan).
  *
  * TEST INFRASTRUCTURE ONLY: a plain, slow, obviously-correct evaluation of the definitions
  * in Sec. 2.1 and Sec. 2.2 of the paper, used by the tests, by the smoke check and as the
@@ -16,7 +16,8 @@
  *
  * Pins (tests/test_oracle_pins.py): exact rational brute force on tiny grids, delta input,
  * constant and linear fields, hand-worked five-point example, scipy.ndimage / torch
- * cross-checks, separable filters, iteration identities.  No function here is unpinned.
+ * cross-checks (also with explicit origins / anchors in 3D), separable filters, iteration identities.
+ * No function here is unpinned.
  */
 #include <stddef.h>
 #ifdef _OPENMP

@@ -300,6 +300,121 @@ def test_conv2d_matches_torch_conv2d(boundary, pad_mode, anchor):
     assert np.allclose(got, want, rtol=0, atol=2e-6)
 
 
+# ---------------------------------------------------------------------------------------
+# 3D filter (Sec. 2.1 with a z index): brute force, delta, library routines, reductions.
+# ---------------------------------------------------------------------------------------
+
+def filter_taps3(filt, ax, ay, az):
+    K, N, M = filt.shape
+    return [(m - ax, n - ay, k - az, filt[k, n, m]) for k in range(K) for n in range(N) for m in range(M)]
+
+
+def seeded_filter3(M, N, K, seed, dtype):
+    return wl.uniform_field((K, N, M), -1.0, 1.0, seed, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("boundary", ["zero", "clamp"])
+@pytest.mark.parametrize("W,H,D,M,N,K,anchor", [
+    (6, 5, 4, 3, 3, 3, None), (5, 4, 3, 2, 2, 2, None), (4, 5, 3, 4, 3, 2, None), (3, 2, 2, 5, 3, 4, None),
+    (5, 4, 3, 3, 2, 2, (0, 0, 0)), (5, 4, 3, 4, 3, 2, (3, 2, 1)), (1, 1, 1, 3, 3, 3, None), (6, 1, 1, 3, 1, 1, None),
+    (4, 3, 5, 1, 1, 4, (0, 0, 3)),
+])
+def test_conv3d_exact_bruteforce(dtype, boundary, W, H, D, M, N, K, anchor):
+    vol = rng_field((D, H, W), 171, dtype)
+    filt = seeded_filter3(M, N, K, 172, dtype)
+    ax, ay, az = (M // 2, N // 2, K // 2) if anchor is None else anchor
+    got = oracle.conv3d(vol, filt, boundary, anchor)
+    exact = exact_taps(vol, filter_taps3(filt, ax, ay, az), boundary)
+    assert_within_ulp(got, exact, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_conv3d_delta_reproduces_filter_point_reflected(dtype):
+    """A unit impulse at p0 puts w[k][n][m] at p0 + anchor - (m, n, k): the filter reflected through the
+    anchor, on every axis -- an axis mixed up with another, or a sign error, moves entries."""
+    M, N, K, W, H, D = 4, 3, 5, 11, 9, 12
+    ax, ay, az = 1, 2, 3
+    filt = seeded_filter3(M, N, K, 173, dtype)
+    x0, y0, z0 = 5, 4, 6
+    vol = np.zeros((D, H, W), dtype=dtype)
+    vol[z0, y0, x0] = 1
+    out = oracle.conv3d(vol, filt, "zero", (ax, ay, az))
+    want = np.zeros_like(vol)
+    for k in range(K):
+        for n in range(N):
+            for m in range(M):
+                want[z0 + az - k, y0 + ay - n, x0 + ax - m] = filt[k, n, m]
+    assert np.array_equal(out, want)
+
+
+@pytest.mark.parametrize("boundary,mode", [("zero", "constant"), ("clamp", "nearest")])
+@pytest.mark.parametrize("MNK,anchor", [((3, 3, 3), None), ((2, 2, 2), None), ((4, 3, 2), None), ((5, 2, 3), (0, 1, 2)),
+                                        ((3, 5, 4), (2, 0, 3)), ((7, 7, 7), None), ((1, 1, 6), None)])
+def test_conv3d_matches_scipy_correlate_with_origin(boundary, mode, MNK, anchor):
+    """scipy centres an even or odd filter at size // 2 and moves it with `origin` (axis order z, y, x):
+    the filter element on the output point is size // 2 + origin."""
+    from scipy import ndimage
+    M, N, K = MNK
+    ax, ay, az = (M // 2, N // 2, K // 2) if anchor is None else anchor
+    vol = rng_field((10, 12, 13), 174, np.float64)
+    filt = seeded_filter3(M, N, K, 175, np.float64)
+    got = oracle.conv3d(vol, filt, boundary, anchor)
+    want = ndimage.correlate(vol, filt, mode=mode, cval=0.0, origin=(az - K // 2, ay - N // 2, ax - M // 2))
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("boundary,pad_mode", [("zero", "constant"), ("clamp", "replicate")])
+@pytest.mark.parametrize("anchor", [None, (0, 0, 0), (3, 1, 1)])
+def test_conv3d_matches_torch_conv3d(boundary, pad_mode, anchor):
+    import torch
+    import torch.nn.functional as F
+    M, N, K = 4, 3, 2
+    ax, ay, az = (M // 2, N // 2, K // 2) if anchor is None else anchor
+    vol = rng_field((7, 9, 11), 176, np.float32)
+    filt = seeded_filter3(M, N, K, 177, np.float32)
+    got = oracle.conv3d(vol, filt, boundary, anchor)
+    t = torch.from_numpy(vol.astype(np.float64))[None, None]
+    t = F.pad(t, (ax, M - 1 - ax, ay, N - 1 - ay, az, K - 1 - az), mode=pad_mode)
+    want = F.conv3d(t, torch.from_numpy(filt.astype(np.float64))[None, None])[0, 0].numpy()
+    assert np.allclose(got, want, rtol=0, atol=2e-6)
+
+
+def test_conv3d_reduces_to_conv2d_and_to_the_stencil():
+    """One filter plane (K = 1) on every z-plane separately is the 2D filter; an odd box without zero
+    entries, anchored at its centre, is the 3D stencil with that coefficient box."""
+    vol = rng_field((5, 8, 9), 178, np.float64)
+    f2 = wl.seeded_filter(4, 3, 179, np.float64)
+    got = oracle.conv3d(vol, f2[None], "clamp", (1, 2, 0))
+    for z in range(vol.shape[0]):
+        assert np.array_equal(got[z], oracle.conv2d(vol[z], f2, "clamp", (1, 2)))
+    box = wl.seeded_coefficients(wl.mask_box(1, 2, 1), 180, np.float64, 0.5, 1.0, normalise=False)
+    assert np.all(box != 0)
+    for bnd in ("zero", "clamp"):
+        assert np.array_equal(oracle.conv3d(vol, box, bnd), oracle.stencil(vol, box, bnd))
+
+
+def test_conv3d_constant_field_enumerates_partial_sums():
+    """Constant input, zero padding: the output at a corner is the sum of the filter entries whose tap
+    stays inside the grid; every anchor / orientation mistake changes which entries those are.  Dyadic
+    values, so the sums are exact."""
+    M, N, K = 3, 2, 4
+    filt = (np.arange(M * N * K, dtype=np.float64).reshape(K, N, M) - 7.0) / 8.0
+    vol = np.full((6, 5, 7), 0.5)
+    for anchor in [(1, 1, 2), (0, 0, 0), (2, 1, 3)]:
+        ax, ay, az = anchor
+        out = oracle.conv3d(vol, filt, "zero", anchor)
+        for (x, y, z) in [(0, 0, 0), (6, 4, 5), (0, 4, 2), (3, 2, 3)]:
+            want = 0.0
+            for k in range(K):
+                for n in range(N):
+                    for m in range(M):
+                        if 0 <= x + m - ax < 7 and 0 <= y + n - ay < 5 and 0 <= z + k - az < 6:
+                            want += filt[k, n, m] * 0.5
+            assert out[z, y, x] == want
+        assert np.array_equal(oracle.conv3d(vol, filt, "clamp", anchor), np.full_like(vol, 0.5 * filt.sum()))
+
+
 def test_stencil3d_matches_torch_conv3d():
     import torch
     import torch.nn.functional as F
