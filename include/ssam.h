@@ -61,6 +61,7 @@ typedef enum { SSAM_BOUNDARY_ZERO = 0, SSAM_BOUNDARY_CLAMP = 1 } ssam_boundary;
 #define SSAM_MAX_FILTER 32   /* largest filter width or height accepted by ssam_conv2d   */
 #define SSAM_MAX_RADIUS 8    /* largest stencil radius per axis                          */
 #define SSAM_MAX_EXTENT (1 << 30)   /* largest W, H or D (and W*H*D at most 2^31-1)      */
+#define SSAM_MAX_FILTER3D 17 /* largest extent of an ssam_conv3d filter along any axis   */
 
 /* 2D filter (paper Sec. 2.1; Listing 1 evaluates it without flipping the filter):
  *     out[y][x] = sum_{n<N} sum_{m<M}  h_filter[n*M + m] * IN(x + m - ax, y + n - ay)
@@ -91,6 +92,19 @@ int ssam_stencil2d(const void *d_in, void *d_out, int W, int H,
 int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,
                    const void *h_coef, int rx, int ry, int rz,
                    int boundary, int dtype, void *hip_stream);
+
+/* 3D filter: the 2D filter of Sec. 2.1 with a third index, the mapping the paper names as its next
+ * (Sec. 6, opening paragraph; Sec. 8), evaluated without a flip like the 2D one:
+ *     out[z][y][x] = sum_{k<K} sum_{n<N} sum_{m<M}  h_filter[(k*N + n)*M + m] * IN(x + m - ax, y + n - ay, z + k - az)
+ * M, N, K are the filter's extents along x, y, z, each 1 .. SSAM_MAX_FILTER3D, even sizes included;
+ * (ax, ay, az) is the filter element placed on the output point, -1 for the default M/2, N/2, K/2.
+ * Every element of the filter is a tap (a zero multiplies, it is not skipped).  Filters that fit a cube
+ * of radius 1, 2 or 3 around their anchor run on the register-cache kernels (3x3x3, 5x5x5, 7x7x7 as
+ * they are, anything else zero-padded inside the smallest such cube); larger ones run on the direct
+ * one-point-per-thread kernel (correct, not fast).  d_in and d_out must not overlap. */
+int ssam_conv3d(const void *d_in, void *d_out, int W, int H, int D,
+                const void *h_filter, int M, int N, int K, int ax, int ay, int az,
+                int boundary, int dtype, void *hip_stream);
 
 /* `steps` Jacobi sweeps (paper Sec. 2.2: s_{i+1} computed from s_i) with two buffers, each
  * launch reading one and writing the other; every grid point is updated each sweep, the
@@ -139,7 +153,8 @@ int ssam_set_tuning(const char *name, int value);
  * ssam_stencil3d with (a, b, c) = (rx, ry, rz); kind 3 = the launch ssam_stencil_iterate uses
  * on a 2D grid with (a, b) = (rx, ry) while c sweeps remain (c <= 0: many); an instance named
  * "..._fusedS" performs S sweeps; kind 4 = the same for a 3D grid with (a, b, c) = (rx, ry, rz)
- * while two or more sweeps remain.  The tile plan follows the paper's overlapped
+ * while two or more sweeps remain; kind 5 = ssam_conv3d with (a, b, c) = (M, N, K) and the default
+ * anchor.  The tile plan follows the paper's overlapped
  * blocking (Sec. 4.5, Sec. 4.7) re-derived for 64 lanes of V columns each. */
 int ssam_describe(int kind, int W, int H, int D, const void *h_coef, int a, int b, int c,
                   int boundary, int dtype, char *buf, int buflen);

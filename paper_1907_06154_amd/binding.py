@@ -19,7 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 SSAM_F32, SSAM_F64 = 0, 1
 SSAM_BOUNDARY_ZERO, SSAM_BOUNDARY_CLAMP = 0, 1
 BOUNDARY = {"zero": SSAM_BOUNDARY_ZERO, "clamp": SSAM_BOUNDARY_CLAMP}
-EXPORTS = ["ssam_conv2d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
+EXPORTS = ["ssam_conv2d", "ssam_conv3d", "ssam_stencil2d", "ssam_stencil3d", "ssam_stencil_iterate",
            "ssam_status_string", "ssam_set_tuning", "ssam_describe", "ssam_probe_copy", "ssam_probe_latency",
            "ssam_scan", "ssam_scan_workspace_bytes", "ssam_scan_static"]
 
@@ -41,6 +41,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
         L.ssam_conv2d.argtypes = [vp, vp, ci, ci, vp, ci, ci, ci, ci, ci, ci, vp]
+        L.ssam_conv3d.argtypes = [vp, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
         L.ssam_stencil2d.argtypes = [vp, vp, ci, ci, vp, ci, ci, ci, ci, vp]
         L.ssam_stencil3d.argtypes = [vp, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, vp]
         L.ssam_stencil_iterate.argtypes = [vp, vp, ci, ci, ci, vp, ci, ci, ci, ci, ci, ci, vp,
@@ -121,6 +122,26 @@ def ssam_conv2d(d_in, filt, boundary: str = "clamp", anchor: Optional[Tuple[int,
     st = lib().ssam_conv2d(d_in.data_ptr(), d_out.data_ptr(), W, H, f.ctypes.data, M, N, ax, ay,
                            BOUNDARY[boundary], code, _stream_ptr(stream))
     _check(st, "ssam_conv2d")
+    return d_out
+
+
+def ssam_conv3d(d_in, filt, boundary: str = "clamp", anchor: Optional[Tuple[int, int, int]] = None,
+                d_out=None, stream=None):
+    """out[z][y][x] = sum_{k,n,m} filt[k][n][m] * IN(x+m-ax, y+n-ay, z+k-az).  d_in: [D][H][W] GPU tensor;
+    filt: host [K][N][M]; anchor (ax, ay, az), default the centre (size // 2 per axis)."""
+    import torch
+    _device_tensor(d_in, "d_in")
+    D, H, W = d_in.shape
+    code = _dtype_code(d_in)
+    f = _host_coef(filt, code)
+    K, N, M = f.shape
+    ax, ay, az = (-1, -1, -1) if anchor is None else anchor
+    if d_out is None:
+        d_out = torch.empty_like(d_in)
+    _device_tensor(d_out, "d_out")
+    st = lib().ssam_conv3d(d_in.data_ptr(), d_out.data_ptr(), W, H, D, f.ctypes.data, M, N, K, ax, ay, az,
+                           BOUNDARY[boundary], code, _stream_ptr(stream))
+    _check(st, "ssam_conv3d")
     return d_out
 
 
@@ -221,6 +242,10 @@ def ssam_describe(kind: str, shape, coef, boundary: str = "zero", remaining: int
         D, H, W = shape
         rx, ry, rz = _radii(coef, 3)
         st = lib().ssam_describe(2, W, H, D, coef.ctypes.data, rx, ry, rz, BOUNDARY[boundary], code, buf, 512)
+    elif kind == "conv3d":
+        D, H, W = shape
+        K, N, M = coef.shape
+        st = lib().ssam_describe(5, W, H, D, coef.ctypes.data, M, N, K, BOUNDARY[boundary], code, buf, 512)
     else:
         raise ValueError(kind)
     _check(st, "ssam_describe")
@@ -251,6 +276,10 @@ def ssam_scan(d_in, d_out=None, d_work=None, stream=None):
     need = int(lib().ssam_scan_workspace_bytes(n, code))
     if d_work is None and need:
         d_work = torch.empty(need, dtype=torch.uint8, device=d_in.device)
+        if stream is not None:
+            # the workspace dies when this function returns while the kernels that use it are still
+            # queued on `stream`: tell the caching allocator, or it may hand the block out again
+            d_work.record_stream(stream)
     wp, wb = (d_work.data_ptr(), d_work.numel() * d_work.element_size()) if d_work is not None else (None, 0)
     _check(lib().ssam_scan(d_in.data_ptr() if n else None, d_out.data_ptr() if n else None, n, code,
                            wp, wb, _stream_ptr(stream)), "ssam_scan")

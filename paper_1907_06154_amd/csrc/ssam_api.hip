@@ -279,7 +279,7 @@ template <typename T>
 const Instance3D* pick3d(const Problem3D& p, int want_variant, int sweeps = 1)
 {
     const T* c = static_cast<const T*>(p.c);
-    int budget = tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
+    int budget = p.dense ? 3 : tap_budget<T>(c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
     if (budget == 0) budget = 1;
     // an instance is compiled for (reach along x, along the strip axis, along the march axis)
     const int strip_r = p.march_y ? p.rz : p.ry, march_r = p.march_y ? p.ry : p.rz;
@@ -350,34 +350,41 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
         Problem2D q{p.in, p.out, p.W, p.H, p.c, 2 * p.rx + 1, 2 * p.ry + 1, p.rx, p.ry, p.boundary, p.dtype, p.stream};
         return run2d(q, true, geo, dry, name);
     }
-    const Instance3D* inst = nullptr;
+    // Taps a compiled shape evaluates: what a launch costs in arithmetic.
+    auto taps = [](const Instance3D& i) {
+        const long n = 2 * i.rx + 1;
+        return i.budget == 1 ? 6L * i.rx + 1 : i.budget == 2 ? n * n * n - 8L * i.rx * i.rx * i.rx : n * n * n;
+    };
+    const Instance3D* inst = nullptr;   // an instance of exactly these radii
+    const Instance3D* cube = nullptr;   // the cheapest compiled shape of equal radii that covers the box, zero-padded
     if (tu.force_generic <= 0) {
         const int v = tu.variant > 0 ? tu.variant : 0;
         inst = p.dtype == SSAM_F32 ? pick3d<float>(p, v) : pick3d<double>(p, v);
         if (!inst && v != 0) inst = p.dtype == SSAM_F32 ? pick3d<float>(p, 0) : pick3d<double>(p, 0);
-    }
-    if (inst) {
-        if (name) *name = inst->name;
-        return status_of(inst->launch(p, tu, geo, dry));
-    }
-    // No instance for these radii: embed the coefficient box, zero-padded, in the cheapest compiled
-    // shape with equal radii that covers it (a star in a wider star, anything in a box).
-    if (tu.force_generic <= 0 && tu.embed_waste != 0) {
-        const int budget = p.dtype == SSAM_F32
-                               ? tap_budget<float>((const float*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz)
-                               : tap_budget<double>((const double*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
-        const int need = p.rx > p.ry ? (p.rx > p.rz ? p.rx : p.rz) : (p.ry > p.rz ? p.ry : p.rz);
-        auto taps = [](const Instance3D& i) {
-            const long n = 2 * i.rx + 1;
-            return i.budget == 1 ? 6L * i.rx + 1 : i.budget == 2 ? n * n * n - 8L * i.rx * i.rx * i.rx : n * n * n;
-        };
-        const Instance3D* cube = nullptr;
-        for (const Instance3D& i : registry3d()) {
-            if (i.dtype != p.dtype || i.rx != i.ry || i.ry != i.rz || i.rx < need || i.budget < budget) continue;
-            if (i.variant != 0 || i.sweeps != 1) continue;
-            if (!cube || taps(i) < taps(*cube)) cube = &i;
+        if (tu.embed_waste != 0) {
+            const int budget = p.dense ? 3 : p.dtype == SSAM_F32
+                                   ? tap_budget<float>((const float*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz)
+                                   : tap_budget<double>((const double*)p.c, 2 * p.rx + 1, 2 * p.ry + 1, 2 * p.rz + 1, p.rx, p.ry, p.rz);
+            const int need = p.rx > p.ry ? (p.rx > p.rz ? p.rx : p.rz) : (p.ry > p.rz ? p.ry : p.rz);
+            for (const Instance3D& i : registry3d()) {
+                if (i.dtype != p.dtype || i.rx != i.ry || i.ry != i.rz || i.rx < need || i.budget < budget) continue;
+                if (i.variant != 0 || i.sweeps != 1) continue;
+                if (!cube || taps(i) < taps(*cube)) cube = &i;
+            }
         }
-        if (cube) {
+    }
+    // The exact instance unless a padded one evaluates fewer taps (a radius-3 star has no instance of
+    // its own: the radius-4 star, 25 taps, beats the radius-3 box, 343); whichever is tried first, a
+    // launcher that does not take this grid (hipErrorNotSupported) leaves the turn to the other.
+    const bool cube_first = cube && cube != inst && (!inst || taps(*cube) < taps(*inst));
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        const bool use_cube = (attempt == 0) == cube_first;
+        if (!use_cube && inst) {
+            if (name) *name = inst->name;
+            const hipError_t e = inst->launch(p, tu, geo, dry);
+            if (e != hipErrorNotSupported) return status_of(e);
+        }
+        if (use_cube && cube && cube != inst) {
             const int R = cube->rx, K = 2 * R + 1;
             const int M = 2 * p.rx + 1, N = 2 * p.ry + 1, L = 2 * p.rz + 1;
             const size_t es = elem(p.dtype);
@@ -391,7 +398,8 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
             q.rx = q.ry = q.rz = R;
             q.c = padded.data();
             if (name) *name = std::string(cube->name) + "+embedded";
-            return status_of(cube->launch(q, tu, geo, dry));
+            const hipError_t e = cube->launch(q, tu, geo, dry);   // the coefficients are copied into the launch arguments
+            if (e != hipErrorNotSupported) return status_of(e);
         }
     }
     if (name) *name = "generic_direct";
@@ -403,11 +411,76 @@ int run3d(const Problem3D& p_in, Geometry* geo, bool dry, std::string* name)
     if (dry) return SSAM_OK;
     hipError_t e = p.dtype == SSAM_F32
                        ? launch_generic<float>((const float*)p.in, (float*)p.out, p.W, p.H, p.D, (const float*)p.c, M,
-                                               N, K, p.rx, p.ry, p.rz, p.boundary, true, p.stream)
+                                               N, K, p.rx, p.ry, p.rz, p.boundary, !p.dense, p.stream)
                        : launch_generic<double>((const double*)p.in, (double*)p.out, p.W, p.H, p.D,
-                                                (const double*)p.c, M, N, K, p.rx, p.ry, p.rz, p.boundary, true,
+                                                (const double*)p.c, M, N, K, p.rx, p.ry, p.rz, p.boundary, !p.dense,
                                                 p.stream);
     return status_of(e);
+}
+
+// 3D filter of extents (M, N, K) anchored at (ax, ay, az).  A cube of odd extent anchored at its
+// centre is the dense coefficient box of a stencil and runs on the compiled box instances (radius 1, 2, 3);
+// any other filter that fits such a cube around its anchor runs zero-padded inside the smallest one
+// (as 2D filters without an instance of their own do); the rest runs on the direct kernel, which
+// takes extents and anchor as they are.
+int run_conv3d(const void* in, void* out, int W, int H, int D, const void* f, int M, int N, int K, int ax, int ay,
+               int az, int boundary, int dtype, hipStream_t stream, Geometry* geo, bool dry, std::string* name)
+{
+    const Tuning tu = current_tuning();
+    const int lo = ax > ay ? (ax > az ? ax : az) : (ay > az ? ay : az);
+    const int hx = M - 1 - ax, hy = N - 1 - ay, hz = K - 1 - az;
+    const int hi = hx > hy ? (hx > hz ? hx : hz) : (hy > hz ? hy : hz);
+    const int R = lo > hi ? lo : hi;
+    const size_t es = elem(dtype);
+    // zero padding costs arithmetic: a cube with more than 8 times the filter's taps (or the "embed_waste"
+    // override) is left to the direct kernel
+    const long waste = tu.embed_waste > 0 ? tu.embed_waste : 8;
+    if (R >= 1 && R <= 3 && tu.force_generic <= 0 && tu.embed_waste != 0 &&
+        (long)(2 * R + 1) * (2 * R + 1) * (2 * R + 1) <= waste * M * N * K) {
+        const int S = 2 * R + 1;
+        std::vector<char> cube((size_t)S * S * S * es, 0);
+        const char* src = static_cast<const char*>(f);
+        for (int k = 0; k < K; ++k)
+            for (int n = 0; n < N; ++n)
+                memcpy(&cube[((((size_t)(k - az + R) * S) + (n - ay + R)) * S + (R - ax)) * es],
+                       src + ((size_t)k * N + n) * M * es, (size_t)M * es);
+        Problem3D p{in, out, W, H, D, cube.data(), R, R, R, boundary, dtype, stream};
+        p.dense = true;
+        std::string inner;
+        const int rc = run3d(p, geo, dry, &inner);
+        if (inner != "generic_direct") {     // a compiled instance took it (the coefficients are copied into the launch arguments)
+            if (name) *name = (M == S && N == S && K == S) ? inner : inner + "+embedded";
+            return rc;
+        }
+    }
+    if (name) *name = "generic_direct";
+    if (geo) {
+        *geo = Geometry();
+        geo->blocks = ceil_div(W, 64) * ceil_div(H, 4) * D;
+    }
+    if (dry) return SSAM_OK;
+    const hipError_t e = dtype == SSAM_F32
+                             ? launch_generic<float>((const float*)in, (float*)out, W, H, D, (const float*)f, M, N, K, ax, ay,
+                                                     az, boundary, false, stream)
+                             : launch_generic<double>((const double*)in, (double*)out, W, H, D, (const double*)f, M, N, K,
+                                                      ax, ay, az, boundary, false, stream);
+    return status_of(e);
+}
+
+// Everything but the grid pointers (the planning query has none).
+int check_conv3d(int W, int H, int D, const void* f, int M, int N, int K, int* ax, int* ay, int* az, int boundary,
+                 int dtype)
+{
+    if (!f) return SSAM_ERR_NULL;
+    if (int e = check_enums(boundary, dtype)) return e;
+    if (int e = check_dims(W, H, D)) return e;
+    if (M <= 0 || N <= 0 || K <= 0 || M > SSAM_MAX_FILTER3D || N > SSAM_MAX_FILTER3D || K > SSAM_MAX_FILTER3D)
+        return SSAM_ERR_SHAPE;
+    if (*ax == -1) *ax = M / 2;
+    if (*ay == -1) *ay = N / 2;
+    if (*az == -1) *az = K / 2;
+    if (*ax < 0 || *ax >= M || *ay < 0 || *ay >= N || *az < 0 || *az >= K) return SSAM_ERR_SHAPE;
+    return SSAM_OK;
 }
 
 int validate_conv(const void* in, const void* out, int W, int H, const void* f, int M, int N, int* ax, int* ay,
@@ -477,6 +550,16 @@ int ssam_stencil3d(const void* d_in, void* d_out, int W, int H, int D, const voi
     if (int e = validate_stencil(d_in, d_out, W, H, D, h_coef, rx, ry, rz, boundary, dtype)) return e;
     Problem3D p{d_in, d_out, W, H, D, h_coef, rx, ry, rz, boundary, dtype, (hipStream_t)hip_stream};
     return run3d(p, nullptr, false, nullptr);
+}
+
+int ssam_conv3d(const void* d_in, void* d_out, int W, int H, int D, const void* h_filter, int M, int N, int K, int ax,
+                int ay, int az, int boundary, int dtype, void* hip_stream)
+{
+    if (!d_in || !d_out) return SSAM_ERR_NULL;
+    if (int e = check_conv3d(W, H, D, h_filter, M, N, K, &ax, &ay, &az, boundary, dtype)) return e;
+    if (overlap(d_in, d_out, (size_t)W * H * D * elem(dtype))) return SSAM_ERR_ALIAS;
+    return run_conv3d(d_in, d_out, W, H, D, h_filter, M, N, K, ax, ay, az, boundary, dtype, (hipStream_t)hip_stream,
+                      nullptr, false, nullptr);
 }
 
 int ssam_stencil_iterate(void* d_a, void* d_b, int W, int H, int D, const void* h_coef, int rx, int ry, int rz,
@@ -599,6 +682,12 @@ int ssam_describe(int kind, int W, int H, int D, const void* h_coef, int a, int 
         int rc = SSAM_OK;
         if (run_fused(p, kMaxFusedSweeps, &g, true, &name, &rc)) return describe(rc, name, g, buf, buflen);
         return describe(run3d(p, &g, true, &name), name, g, buf, buflen);
+    }
+    if (kind == 5) {   // ssam_conv3d with (a, b, c) = (M, N, K) and the default anchor
+        int ax = -1, ay = -1, az = -1;
+        if (int e = check_conv3d(W, H, D, h_coef, a, b, c, &ax, &ay, &az, boundary, dtype)) return e;
+        return describe(run_conv3d(nullptr, nullptr, W, H, D, h_coef, a, b, c, ax, ay, az, boundary, dtype, nullptr, &g,
+                                   true, &name), name, g, buf, buflen);
     }
     return SSAM_ERR_ENUM;
 }

@@ -51,6 +51,7 @@ struct Problem3D {
     int boundary, dtype;
     hipStream_t stream;
     bool march_y = false;  // march along y with the register strip along z (instances see ry, rz exchanged)
+    bool dense = false;    // filter semantics: every element of the box is a tap, zeros included
 };
 
 // Tile geometry of one launch (all host arithmetic; also reported by ssam_describe).

@@ -378,6 +378,9 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     }
 }
 
+// Fallback of a shape that has no other compiled instance: the dispatcher then takes the direct kernel.
+inline hipError_t launch3d_unavailable(const Problem3D&, const Tuning&, Geometry*, bool) { return hipErrorNotSupported; }
+
 // FALLBACK: the launcher of the instance that takes what this kernel does not (rows that are not a
 // multiple of 16 bytes, unaligned base pointers, planes beyond 4 GiB).
 template <typename T, int P, int NW, int R, int BUDGET, int NBUF, int NT, Launch3DFn FALLBACK>

@@ -56,6 +56,26 @@ def test_conv2d_validation(L):
     assert conv(L, d_out=FAKE_A + 64 * 64 * 4) != 5
 
 
+def test_conv3d_validation_and_plan(L):
+    f = np.ones((3, 3, 3), dtype=np.float32)
+
+    def call(d_in=FAKE_A, d_out=FAKE_B, W=32, H=32, D=32, filt=f, M=3, N=3, K=3, ax=-1, ay=-1, az=-1, boundary=1, dtype=0):
+        return L.ssam_conv3d(d_in, d_out, W, H, D, None if filt is None else filt.ctypes.data, M, N, K, ax, ay, az,
+                             boundary, dtype, None)
+
+    assert call(d_in=None) == 1 and call(d_out=None) == 1 and call(filt=None) == 1
+    assert call(W=0) == 2 and call(D=-1) == 2 and call(W=2048, H=2048, D=1024) == 2
+    assert call(M=0) == 3 and call(K=18) == 3 and call(ax=3) == 3 and call(az=-2) == 3
+    assert call(boundary=3) == 4 and call(dtype=2) == 4
+    assert call(d_out=FAKE_A) == 5 and call(d_out=FAKE_A + 32 * 32 * 32 * 4 - 4) == 5
+    # the plan: compiled cubes, embedding within a waste limit, the direct kernel for the rest
+    for shape, prefix in (((3, 3, 3), "float_r111_b3"), ((5, 5, 5), "float_r222_b3"), ((7, 7, 7), "float_r333_b3")):
+        assert ssam.ssam_describe("conv3d", (64, 64, 64), np.ones(shape, dtype=np.float32), "clamp").split()[0].startswith(prefix)
+    assert ssam.ssam_describe("conv3d", (64, 64, 64), np.ones((2, 2, 2)), "zero").split()[0] == "double_r111_b3_p4w8star_ring3nt2+embedded"
+    for shape in ((9, 9, 9), (17, 17, 17), (6, 1, 1), (8, 8, 2)):
+        assert ssam.ssam_describe("conv3d", (64, 64, 64), np.ones(shape), "zero").split()[0] == "generic_direct"
+
+
 def test_stencil_validation(L):
     c = np.ones(27, dtype=np.float64)
     cp = c.ctypes.data

@@ -224,6 +224,33 @@ def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
             ssam.ssam_set_tuning(k, -1)
 
 
+CONV3D_CASES = [((3, 3, 3), None), ((5, 5, 5), None), ((7, 7, 7), None), ((2, 2, 2), None), ((4, 3, 2), None),
+                ((3, 3, 3), (0, 0, 0)), ((4, 4, 4), (3, 1, 2)), ((5, 2, 3), (4, 0, 1)), ((1, 1, 6), None), ((9, 9, 9), None),
+                ((17, 2, 1), (16, 1, 0)), ((6, 6, 6), None)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("boundary", ["clamp", "zero"])
+def test_conv3d(ssam, dtype, boundary):
+    """3D filters of odd and even extents, centred and off-centre anchors: the cubes that are compiled
+    instances, those embedded in one, and those left to the direct kernel; rows that are and are not a
+    multiple of 16 bytes."""
+    for k, ((M, N, K), anchor) in enumerate(CONV3D_CASES):
+        filt = wl.uniform_field((K, N, M), -1.0, 1.0, 660 + k, dtype)
+        for shape in ((19, 23, 132), (9, 10, 67), (3, 2, 4)):
+            vol = wl.uniform_field(shape, 0.0, 1.0, 670 + k, dtype)
+            name = ssam.ssam_describe("conv3d", shape, filt, boundary).split()[0]
+            print(f"conv3d {np.dtype(dtype).name} {M}x{N}x{K} anchor {anchor} {boundary} grid {shape} {name}", flush=True)
+            got = host(ssam.ssam_conv3d(dev(vol), filt, boundary, anchor))
+            want = oracle.conv3d(vol, filt, boundary, anchor)
+            assert_parity(got, want, filt, 1.0, f"conv3d {M}x{N}x{K} {anchor} {boundary} {shape}")
+    # a zero in the filter is a tap like any other: same result as the stencil with that box (finite inputs)
+    box = wl.seeded_coefficients(wl.mask_star(1, 1, 1), 680, dtype)
+    vol = wl.uniform_field((12, 20, 136), -1.0, 1.0, 681, dtype)
+    assert_parity(host(ssam.ssam_conv3d(dev(vol), box, boundary)), oracle.conv3d(vol, box, boundary), box, 1.0, "zeros are taps")
+    assert ssam.ssam_describe("conv3d", vol.shape, box, boundary).split()[0].startswith(("float_r111_b3", "double_r111_b3"))
+
+
 STAR_SHAPES = [(33, 70, 260), (75, 9, 512), (10, 40, 4), (5, 3, 8), (13, 37, 132), (21, 66, 1028)]
 
 
