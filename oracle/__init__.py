@@ -15,14 +15,21 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ssam_oracle.c")
-_LIB = os.path.join(_HERE, "libssam_oracle.so")
+_LIB = os.environ.get("SSAM_ORACLE_LIB") or os.path.join(_HERE, "libssam_oracle.so")   # override: a sanitizer build
 _lib: Optional[ctypes.CDLL] = None
 
 BOUNDARY = {"zero": 0, "clamp": 1}
 
 
-def build(force: bool = True) -> str:
-    """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path."""
+def build(force: bool = True, sanitize: Optional[str] = None) -> str:
+    """Compile the oracle with gcc (-O2 -fopenmp).  Returns the library path.
+    sanitize: path of a second library to build with -fsanitize=address,undefined instead; run the CPU
+    tests against it with SSAM_ORACLE_LIB=<path> and gcc's libasan.so / libubsan.so in LD_PRELOAD."""
+    if sanitize:
+        cmd = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared", "-fsanitize=address,undefined",
+               "-fno-omit-frame-pointer", "-Wall", "-Wextra", "-o", sanitize, _SRC]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+        return sanitize
     if force or not os.path.exists(_LIB):
         cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
                "-Wall", "-Wextra", "-o", _LIB, _SRC]

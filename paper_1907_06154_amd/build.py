@@ -58,7 +58,8 @@ def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB, increm
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(lambda s: _compile(s, list(extra), incremental), srcs))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
+    link_extra = [a for a in extra if "sanitize" in a]      # a sanitizer build links its runtime too
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, "-o", lib, *objs]
     subprocess.run(cmd, check=True)
     if verbose:
         print(f"built {lib} from {len(srcs)} translation units")
@@ -66,7 +67,14 @@ def build(verbose: bool = False, jobs: int = 8, extra=(), lib: str = LIB, increm
 
 
 if __name__ == "__main__":
-    # python -m paper_1907_06154_amd.build [output.so] [-DNAME ...] [--incremental]   (extra defines: experiments)
+    # python -m paper_1907_06154_amd.build [output.so] [-DNAME ...] [--incremental] [--sanitize-host]
+    #   -DNAME: extra defines (experiments).  --sanitize-host: AddressSanitizer + UBSan on the HOST code only
+    #   (validation, planner, dispatch; device code is compiled as usual), for a CPU run of the host-only
+    #   tests with clang's asan runtime preloaded.
     args = sys.argv[1:]
     out = next((a for a in args if a.endswith(".so")), LIB)
-    build(verbose=True, extra=[a for a in args if a.startswith("-D")], lib=out, incremental="--incremental" in args)
+    extra = [a for a in args if a.startswith("-D")]
+    if "--sanitize-host" in args:
+        extra += ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+                  "-fno-omit-frame-pointer", "-g"]
+    build(verbose=True, extra=extra, lib=out, incremental="--incremental" in args)

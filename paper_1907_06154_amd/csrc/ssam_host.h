@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/ssam.h"
+#include "../../include/ssam_tuning.h"
 
 #define SSAM_CAT_(a, b) a##b
 #define SSAM_CAT(a, b) SSAM_CAT_(a, b)

@@ -224,7 +224,7 @@ def resources(out_md: str, only_default: bool = True) -> None:
             raise SystemExit(res.stderr)
         cur = None
         for line in res.stderr.splitlines():
-            m = re.search(r"remark: [^ ]+ (Function Name|VGPRs|AGPRs|SGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|LDS Size \[bytes/block\]): (\S+)", line)
+            m = re.search(r"remark:\s+(Function Name|VGPRs|AGPRs|SGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|LDS Size \[bytes/block\]): (\S+)", line)
             if not m:
                 continue
             if m.group(1) == "Function Name":
@@ -238,8 +238,8 @@ def resources(out_md: str, only_default: bool = True) -> None:
            "    python -m paper_1907_06154_amd.profiling resources profiles/kernel_resources.md\n",
            "(`hipcc --offload-arch=gfx950 -O3 ... --cuda-device-only -Rpass-analysis=kernel-resource-usage` per translation unit.)  "
            "VGPRs + AGPRs share one file of 512 registers per SIMD lane: waves per SIMD = floor(512 / (VGPRs + AGPRs, rounded up "
-           "to 8)), at most 8; a block's LDS also limits the blocks per compute unit (160 KiB).  Scratch is 0 for every kernel a "
-           "default dispatch uses.\n",
+           "to 8)), at most 8; a block's LDS also limits the blocks per compute unit (160 KiB).  Kernels with scratch (register "
+           "spills): " + (", ".join(f"`{r['kernel']}` ({r.get('ScratchSize')} bytes per lane)" for r in rows if r.get("ScratchSize", "0") != "0") or "none") + ".\n",
            "| translation unit | kernel | VGPRs | AGPRs | SGPRs | LDS bytes / block | scratch bytes / lane | waves / SIMD |\n|---|---|---|---|---|---|---|---|"]
     for r in rows:
         out.append(f"| {r['file']} | `{r['kernel']}` | {r.get('VGPRs', '')} | {r.get('AGPRs', '')} | {r.get('SGPRs', '')} | "

@@ -82,6 +82,19 @@ def test_config2_full_size(ssam, case):
     check(ssam, case, windows_2d(8192, 48, 320))
 
 
+@pytest.mark.parametrize("name", ["c2_conv3x3_f32", "c2_conv9x9_f32", "c2_conv20x20_f32", "c2_conv11x3_f32"])
+def test_config2_full_grid(ssam, name):
+    """Every one of the 67 M outputs of a configuration-2 pass against the oracle's full field (one
+    bandwidth-bound filter, the two matrix-core ones at either end of their range, and the wide one);
+    the oracle needs a few seconds per filter on the GPU machine's host cores."""
+    case = next(c for c in wl.config2() if c.name == name)
+    res = run_gpu(ssam, case).cpu().numpy()
+    print(f"{name}: oracle on the full {case.shape} grid", flush=True)
+    want = oracle.conv2d(field_of(case), case.coef, case.boundary)
+    err = assert_parity(res, want, case.coef, 1.0, f"{name} full grid")
+    print(f"{name}: worst normalised error over {res.size} points {err:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("case", wl.config3(), ids=lambda c: c.name)
 def test_config3_full_size_100_sweeps(ssam, case):
     wins = windows_2d(8192, 24, 40)

@@ -224,6 +224,22 @@ def test_tile_geometry_overrides_do_not_change_results(ssam, tuning):
             ssam.ssam_set_tuning(k, -1)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_table3_2d64pt(ssam, dtype):
+    """The one Table 3 shape no radius describes, an 8x8 box: a dense 8x8 filter with the default anchor
+    (4, 4), on an instance of its own in both precisions."""
+    case = next(c for c in wl.table3(dtypes=(dtype,)) if "2d64pt" in c.name)
+    assert case.coef.shape == (8, 8) and abs(float(case.coef.sum()) - 1.0) < 1e-5
+    for k, (H, W) in enumerate(SHAPES_2D):
+        img = wl.uniform_field((H, W), -1.0, 1.0, 690 + k, dtype)
+        name = ssam.ssam_describe("conv2d", img.shape, case.coef, case.boundary).split()[0]
+        assert "_M8N8_" in name and "embedded" not in name, name
+        for bnd in ("zero", "clamp"):
+            print(f"2d64pt {np.dtype(dtype).name} {bnd} grid {H}x{W} {name}", flush=True)
+            got = host(ssam.ssam_conv2d(dev(img), case.coef, bnd))
+            assert_parity(got, oracle.conv2d(img, case.coef, bnd), case.coef, 1.0, f"2d64pt {bnd} {H}x{W}")
+
+
 CONV3D_CASES = [((3, 3, 3), None), ((5, 5, 5), None), ((7, 7, 7), None), ((2, 2, 2), None), ((4, 3, 2), None),
                 ((3, 3, 3), (0, 0, 0)), ((4, 4, 4), (3, 1, 2)), ((5, 2, 3), (4, 0, 1)), ((1, 1, 6), None), ((9, 9, 9), None),
                 ((17, 2, 1), (16, 1, 0)), ((6, 6, 6), None)]

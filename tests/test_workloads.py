@@ -61,6 +61,7 @@ def test_config_catalogue():
     t3 = {c.name: c.taps for c in cfg["table3"]}
     assert t3["t3_2d5pt_f32"] == 5 and t3["t3_2ds25pt_f64"] == 25 and t3["t3_2d121pt_f32"] == 121
     assert t3["t3_3d13pt_f64"] == 13 and t3["t3_3d125pt_f32"] == 125 and t3["t3_poisson_f64"] == 19
+    assert t3["t3_2d64pt_f32"] == 64 and t3["t3_2d64pt_f64"] == 64
     c1 = cfg["config1"][0]
     assert c1.coef.max() < 0.25 and c1.coef[c1.coef != 0].min() > 0
     assert cfg["config2"][0].boundary == "clamp" and cfg["config3"][0].steps == 100

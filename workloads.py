@@ -251,9 +251,10 @@ def filter_sweep(n: int = 8192) -> List[Case]:
 
 
 def table3(n2: int = 8192, n3: int = 512, steps: int = 10, dtypes=(np.float32, np.float64)) -> List[Case]:
-    """The stencil shapes of Table 3 that a radius describes (2d64pt is not one of them): 2D stars of
-    order 1..6, 2D boxes of order 2, 4, 5, 3D stars of order 1, 2, 3D boxes of order 1, 2 and the
-    19-point shape, in both precisions, `steps` sweeps with seeded coefficients of sum 1."""
+    """The stencil shapes of Table 3: 2D stars of order 1..6, 2D boxes of order 2, 4, 5, 3D stars of order
+    1, 2, 3D boxes of order 1, 2 and the 19-point shape, in both precisions, `steps` sweeps with seeded
+    coefficients of sum 1; and `2d64pt`, the one shape no radius describes: an 8x8 box, run as one pass of
+    a dense 8x8 filter (anchor (4, 4), zero padding) with coefficients of sum 1."""
     specs2 = [("2d5pt", mask_star(1, 1)), ("2d9pt", mask_star(2, 2)), ("2d13pt", mask_star(3, 3)),
               ("2d17pt", mask_star(4, 4)), ("2d21pt", mask_star(5, 5)), ("2ds25pt", mask_star(6, 6)),
               ("2d25pt", mask_box(2, 2)), ("2d81pt", mask_box(4, 4)), ("2d121pt", mask_box(5, 5))]
@@ -265,6 +266,9 @@ def table3(n2: int = 8192, n3: int = 512, steps: int = 10, dtypes=(np.float32, n
         for i, (nm, m) in enumerate(specs2):
             out.append(Case(f"t3_{nm}_{tag}", "stencil2d", dt, (n2, n2), (-1.0, 1.0), 5,
                             seeded_coefficients(m, 300 + i, dt), "zero", steps, f"Table 3 {nm}"))
+        f64pt = seeded_filter(8, 8, 340, np.float64, 0.0, 1.0)
+        out.append(Case(f"t3_2d64pt_{tag}", "conv2d", dt, (n2, n2), (-1.0, 1.0), 5, (f64pt / f64pt.sum()).astype(dt),
+                        "zero", 1, "Table 3 2d64pt"))
         for i, (nm, m) in enumerate(specs3):
             out.append(Case(f"t3_{nm}_{tag}", "stencil3d", dt, (n3, n3, n3), (-1.0, 1.0), 6,
                             seeded_coefficients(m, 320 + i, dt), "zero", steps, f"Table 3 {nm}"))
