@@ -224,7 +224,7 @@ def resources(out_md: str, only_default: bool = True) -> None:
             raise SystemExit(res.stderr)
         cur = None
         for line in res.stderr.splitlines():
-            m = re.search(r"remark:\s+(Function Name|VGPRs|AGPRs|SGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|LDS Size \[bytes/block\]): (\S+)", line)
+            m = re.search(r"remark:\s+(Function Name|VGPRs|AGPRs|TotalSGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|LDS Size \[bytes/block\]): (\S+)", line)
             if not m:
                 continue
             if m.group(1) == "Function Name":
@@ -242,7 +242,7 @@ def resources(out_md: str, only_default: bool = True) -> None:
            "spills): " + (", ".join(f"`{r['kernel']}` ({r.get('ScratchSize')} bytes per lane)" for r in rows if r.get("ScratchSize", "0") != "0") or "none") + ".\n",
            "| translation unit | kernel | VGPRs | AGPRs | SGPRs | LDS bytes / block | scratch bytes / lane | waves / SIMD |\n|---|---|---|---|---|---|---|---|"]
     for r in rows:
-        out.append(f"| {r['file']} | `{r['kernel']}` | {r.get('VGPRs', '')} | {r.get('AGPRs', '')} | {r.get('SGPRs', '')} | "
+        out.append(f"| {r['file']} | `{r['kernel']}` | {r.get('VGPRs', '')} | {r.get('AGPRs', '')} | {r.get('TotalSGPRs', '')} | "
                    f"{r.get('LDS Size', '')} | {r.get('ScratchSize', '')} | {r.get('Occupancy', '')} |")
     open(out_md, "w").write("\n".join(out) + "\n")
     print(f"{len(rows)} kernels -> {out_md}")
