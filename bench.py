@@ -599,6 +599,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
     ap.add_argument("--min-case-seconds", type=float, default=0.5, help="GPU time every per-kernel figure is measured over")
     ap.add_argument("--headline-only", action="store_true", help="default workload: skip configurations 1, 3, 4, 5")
+    ap.add_argument("--variant", type=int, default=-1,
+                    help="tuning variant for the whole run (e.g. 5: vector-unit instances of the matrix-core filters)")
     ap.add_argument("--tune", default=None, help='"knob=v1,v2;knob2=..." : time the selected cases under tuning overrides')
     args = ap.parse_args()
 
@@ -618,6 +620,8 @@ def main() -> int:
     ssam.lib()
     torch.cuda.set_device(0)
 
+    if args.variant >= 0:
+        ssam.ssam_set_tuning("variant", args.variant)
     if args.tune is not None:
         return tune(ssam, wl, torch, args)
     if args.workload == "scan":

@@ -5,6 +5,8 @@ profiles/measured_traffic.json, the HBM bytes per launch that bench.py reports a
     python -m paper_1907_06154_amd.profiling sq <counter dir> [<counter dir> ...] <out.md>
     python -m paper_1907_06154_amd.profiling lds <counter dir> [<counter dir> ...] <out.md>
     python -m paper_1907_06154_amd.profiling resources <out.md>
+    python -m paper_1907_06154_amd.profiling catalogue <single.json> <default.json> <out.md>
+    python -m paper_1907_06154_amd.profiling sweep <default.json> <variant5.json> <out.md>
 
 `summarize` expects three rocprofv3 runs of the same bench.py command (the commands are written
 into the summary), each with its bench.py output saved beside it:
@@ -248,6 +250,62 @@ def resources(out_md: str, only_default: bool = True) -> None:
     print(f"{len(rows)} kernels -> {out_md}")
 
 
+def catalogue(single_json: str, default_json: str, out_md: str) -> None:
+    """Table 3 catalogue: two bench.py runs of --workload table3 (one sweep per launch / default)."""
+    a, b = json.load(open(single_json)), json.load(open(default_json))
+    out = ["# bench.py timing: Stencil shapes of Table 3 (paper Sec. 6.3): 2D on 8192^2, 3D on 512^3, fp32 and fp64, zero padding\n",
+           "One MI355X, HIP events on the launch stream, medians.  Two runs: one sweep per launch, and the library's default, where "
+           "`ssam_stencil_iterate` runs several sweeps per launch for the shapes that have a multi-sweep instance (2D r <= 6, 3D "
+           "r = 1 and the fp32 13-point star).  `2d64pt`, an 8x8 box, runs as one pass of a dense 8x8 filter.\n",
+           f"    python bench.py --workload table3 --no-cpu-baseline --steps {a['steps']} --fuse-sweeps 0 > {single_json}\n"
+           f"    python bench.py --workload table3 --no-cpu-baseline --steps {b['steps']} > {default_json}\n"
+           f"    python -m paper_1907_06154_amd.profiling catalogue {single_json} {default_json} {os.path.relpath(out_md, ROOT)}\n",
+           f"Whole-step throughput {a['value']:.1f} GStencil/s ({a['ms_per_step']:.2f} ms per step) with single sweeps, "
+           f"{b['value']:.1f} GStencil/s ({b['ms_per_step']:.2f} ms) by default; plain grid-stride copy on the first case's buffers "
+           f"{b['plain_copy_GBps']:.0f} GB/s.\n",
+           "Single-sweep columns: launch time, GStencil/s, algorithmic GB/s (one read + one write per sweep) as a fraction of "
+           "8 TB/s, TFLOP/s as a fraction of the published vector peak (157.3 fp32, 78.6 fp64).  Default columns: instance used "
+           "for most launches, launches per run, GStencil/s and the gain.\n",
+           "| case | single-sweep instance | launch us | GStencil/s | GB/s | of 8 TB/s | TFLOP/s | of peak | bound | default instance "
+           "| launches | GStencil/s | gain |\n|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    kb = {k["case"]: k for k in b["kernels"]}
+    for k in a["kernels"]:
+        f = kb[k["case"]]
+        out.append(f"| {k['case']} | `{k['kernel']}` | {k['launch_ms'] * 1e3:.1f} | {k['gstencil_per_s']:.1f} | {k['hbm_GBps']:.0f} | "
+                   f"{k['hbm_frac']:.3f} | {k['alu_TFLOPs']:.1f} | {k['alu_frac']:.3f} | {k['bound']} | `{f['kernel']}` | "
+                   f"{f['launches_per_step']} | {f['gstencil_per_s']:.1f} | {f['gstencil_per_s'] / k['gstencil_per_s']:.2f}x |")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
+def sweep(default_json: str, vector_json: str, out_md: str) -> None:
+    """Filter sweep 2x2 .. 20x20: bench.py --workload filter_sweep by default and with --tune-variant 5
+    (the vector-unit instances of the filters whose defaults run on the matrix cores)."""
+    a, v = json.load(open(default_json)), json.load(open(vector_json))
+    out = ["# bench.py timing: Filter sweep 2x2 .. 20x20 (paper Sec. 6.2), 8192x8192 fp32, clamp\n",
+           "One MI355X, HIP events on the launch stream, medians per launch; the input is one tensor (warm in the memory-side "
+           "cache; `bench.py` without arguments reports the configuration-2 filters cold).  Second run: tuning variant 5, the "
+           "vector-unit instances of the filters whose default instances (`...mx`) evaluate their products on the matrix cores "
+           "(shapes without such an alternative run their default in both).\n",
+           f"    python bench.py --workload filter_sweep --no-cpu-baseline --steps {a['steps']} --warmup {a['warmup']} > {default_json}\n"
+           f"    python bench.py --workload filter_sweep --no-cpu-baseline --steps {v['steps']} --warmup {v['warmup']} --variant 5 > {vector_json}\n"
+           f"    python -m paper_1907_06154_amd.profiling sweep {default_json} {vector_json} {os.path.relpath(out_md, ROOT)}\n",
+           f"Whole-step throughput {a['value']:.1f} GStencil/s, {a['ms_per_step']:.2f} ms per step (variant 5: {v['value']:.1f}, "
+           f"{v['ms_per_step']:.2f} ms); plain grid-stride copy on the same buffers {a['plain_copy_GBps']:.0f} GB/s.\n",
+           "Fractions: algorithmic GB/s of 8 TB/s; TFLOP/s of 157.3 (the published fp32 vector peak, which assumes packed FMA and "
+           "equals the fp32 matrix peak; the non-packed vector rate reachable here is 78.6).\n",
+           "| case | kernel instance | launch us | GStencil/s | algorithmic GB/s | of 8 TB/s | TFLOP/s | of 157.3 | bound | "
+           "vector-unit instance | launch us | GStencil/s | of 78.6 TFLOP/s |\n|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    kv = {k["case"]: k for k in v["kernels"]}
+    for k in a["kernels"]:
+        u = kv[k["case"]]
+        out.append(f"| {k['case']} | `{k['kernel']}` | {k['launch_ms'] * 1e3:.1f} | {k['gstencil_per_s']:.1f} | {k['hbm_GBps']:.0f} | "
+                   f"{k['hbm_frac']:.3f} | {k['alu_TFLOPs']:.1f} | {k['alu_frac']:.3f} | {k['bound']} | `{u['kernel']}` | "
+                   f"{u['launch_ms'] * 1e3:.1f} | {u['gstencil_per_s']:.1f} | {u['alu_TFLOPs'] / 78.6:.3f} |")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
 def main(argv) -> int:
     if len(argv) >= 3 and argv[0] == "summarize":
         title = argv[argv.index("--title") + 1]
@@ -257,6 +315,10 @@ def main(argv) -> int:
         sq(argv[1:-1], argv[-1])
     elif len(argv) >= 3 and argv[0] == "lds":
         lds(argv[1:-1], argv[-1])
+    elif len(argv) == 4 and argv[0] == "catalogue":
+        catalogue(argv[1], argv[2], argv[3])
+    elif len(argv) == 4 and argv[0] == "sweep":
+        sweep(argv[1], argv[2], argv[3])
     elif len(argv) == 2 and argv[0] == "resources":
         resources(argv[1])
     else:
