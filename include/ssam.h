@@ -86,7 +86,7 @@ int ssam_stencil2d(const void *d_in, void *d_out, int W, int H,
  *     out[z][y][x] = sum  h_coef[((dz+rz)*(2ry+1) + (dy+ry))*(2rx+1) + (dx+rx)] * IN(x+dx, y+dy, z+dz)
  * with the same zero-means-no-tap rule; Above = dz -1, Below = dz +1.
  * Shapes with a compiled instance (or that fit zero-padded inside one: stars up to radius 4, boxes
- * up to radius 2) run on the register-cache kernels; any other, up to SSAM_MAX_RADIUS per axis, runs
+ * up to radius 3) run on the register-cache kernels; any other, up to SSAM_MAX_RADIUS per axis, runs
  * on a direct one-point-per-thread kernel (correct, not fast) whose taps travel in the launch
  * arguments, in as many launches on hip_stream as the tap count needs. */
 int ssam_stencil3d(const void *d_in, void *d_out, int W, int H, int D,

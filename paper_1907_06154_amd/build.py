@@ -19,6 +19,9 @@ LIB = os.path.join(HERE, "libssam.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # matrix-core accumulators stay in ordinary vector registers: the lane shifts read them there, and
+         # the moves to and from the accumulation registers cost 3-7 % on the 7x7 ... 20x20 filters
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
 
 

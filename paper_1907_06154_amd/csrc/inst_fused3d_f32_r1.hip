@@ -1,6 +1,7 @@
-// Two-sweep (temporally blocked) radius-1 3D stencil instances, f32: inst_fused3d_f32_r1.hip
-// Variant 0 is the faster of the two on 512^3 (with or without a second plane buffer); variant 1 the other.
+// Two-sweep (temporally blocked) radius-1 3D stencil instance, f32: inst_fused3d_f32_r1.hip
+// Only the 7-point star has one: for the 19- and 27-point shapes and the radius-2 star the
+// block-cooperative single-sweep kernel is as fast or faster on 512^3 (19-point: 714 against 688
+// GStencil/s, radius-2 star: 706 against 634).
 #include "ssam_kernel3d_fused.h"
 
 SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 1, 0, 2, 0);
-SSAM_INSTANCE_3D_FUSED(float, SSAM_F32, 4, 4, 1, 1, 1, 2, 0, 2, 0);

@@ -255,8 +255,8 @@ def catalogue(single_json: str, default_json: str, out_md: str) -> None:
     a, b = json.load(open(single_json)), json.load(open(default_json))
     out = ["# bench.py timing: Stencil shapes of Table 3 (paper Sec. 6.3): 2D on 8192^2, 3D on 512^3, fp32 and fp64, zero padding\n",
            "One MI355X, HIP events on the launch stream, medians.  Two runs: one sweep per launch, and the library's default, where "
-           "`ssam_stencil_iterate` runs several sweeps per launch for the shapes that have a multi-sweep instance (2D r <= 6, 3D "
-           "r = 1 and the fp32 13-point star).  `2d64pt`, an 8x8 box, runs as one pass of a dense 8x8 filter.\n",
+           "`ssam_stencil_iterate` runs several sweeps per launch for the shapes that have a multi-sweep instance (2D r <= 6; 3D "
+           "r = 1: the three fp64 shapes and the fp32 7-point star).  `2d64pt`, an 8x8 box, runs as one pass of a dense 8x8 filter.\n",
            f"    python bench.py --workload table3 --no-cpu-baseline --steps {a['steps']} --fuse-sweeps 0 > {single_json}\n"
            f"    python bench.py --workload table3 --no-cpu-baseline --steps {b['steps']} > {default_json}\n"
            f"    python -m paper_1907_06154_amd.profiling catalogue {single_json} {default_json} {os.path.relpath(out_md, ROOT)}\n",
