@@ -417,24 +417,26 @@ __device__ __forceinline__ void systolic_rows(const Rows& r, ConstPtr<T> w,
 // vector unit is left with the lane shifts.  N + 3 instructions replace 4 N fused multiply-adds
 // per filter column and output column; rows k that meet no tap of the column are skipped.
 //
-// The a operands come from a table in LDS, laid out for this: tab[(m * (N + 3) + k) * 4 + q] =
-// w[k - q][m], 0 outside the filter; each lane reads entry q = lane % 4 (four addresses per read,
-// broadcast, no conflict).  The caller fills the table once per workgroup (fill_mfma_weights).
+// The a operands come from a table in LDS, laid out for this: tab[(m * 4 + q) * CP + k] = w[k - q][m], 0
+// outside the filter, CP = N + 3 rounded up to a multiple of four; each lane reads the entries q = lane % 4
+// of four consecutive window rows k with one 16-byte read (four addresses per read, broadcast, no
+// conflict).  The caller fills the table once per workgroup (fill_mfma_weights).
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 template <class Mask>
 struct MfmaWeights {
     static constexpr int kRows = Mask::kN + 3;              // rows of the window of four positions
-    static constexpr int kWords = Mask::kM * kRows * 4;
+    static constexpr int kPitch = (kRows + 3) / 4 * 4;      // words per (filter column, q): whole 16-byte pieces
+    static constexpr int kWords = Mask::kM * 4 * kPitch;
 };
 
 // Workgroup-cooperative; the caller synchronises afterwards.
 template <class Mask>
 __device__ __forceinline__ void fill_mfma_weights(ConstPtr<float> w, float* tab)
 {
-    constexpr int N = Mask::kN, C = MfmaWeights<Mask>::kRows;
+    constexpr int N = Mask::kN, CP = MfmaWeights<Mask>::kPitch;
     for (int e = threadIdx.x; e < MfmaWeights<Mask>::kWords; e += blockDim.x) {
-        const int q = e & 3, k = (e >> 2) % C, m = (e >> 2) / C;
+        const int k = e % CP, q = (e / CP) & 3, m = e / (4 * CP);
         const int n = k - q;
         tab[e] = (n >= 0 && n < N && Mask::tap(n, m)) ? w[Mask::widx(n, m)] : 0.0f;
     }
@@ -448,136 +450,174 @@ __host__ __device__ constexpr bool window_row_meets_column(int k, int m)
     return false;
 }
 
-// column_products on the matrix cores: tab_lane = table + lane % 4; s[j] holds the four window
-// sums of output column j.  Two filter columns are evaluated together (HAS2 = false: one), row by
-// row: a column COL lane-columns away from the output column feeds only V - |COL| of the V sums, and
-// a dependent instruction can only follow after 12 cycles where an independent one follows after 8,
-// so the columns COL and COL + V, which feed complementary sums, are interleaved.
-template <int V, class Mask, int DX1, int COL1, bool HAS2, int DX2, int COL2, class Rows>
-__device__ __forceinline__ void column_products_mfma(const Rows& r, const float* tab_lane, v4f (&s)[V], bool (&set)[V])
-{
-    constexpr int C = MfmaWeights<Mask>::kRows, m1 = Mask::kAX + DX1, m2 = HAS2 ? Mask::kAX + DX2 : 0;
-    // the opaque zero pins the table reads of these filter columns to this place: otherwise the
-    // compiler requests the whole table ahead and spills the registers it needs for that
-    const float* col = tab_lane + opaque_zero();
-    float a1[C], a2[HAS2 ? C : 1];   // the operands are requested together, so that one wait covers them all
-#pragma unroll
-    for (int k = 0; k < C; ++k) {
-        if (window_row_meets_column<Mask>(k, m1)) a1[k] = col[(m1 * C + k) * 4];
-        if (HAS2 && window_row_meets_column<Mask>(k, m2)) a2[HAS2 ? k : 0] = col[(m2 * C + k) * 4];
-    }
-    __builtin_amdgcn_sched_barrier(0);   // or the scheduler moves every read next to its use and waits for each
-#pragma unroll
-    for (int k = 0; k < C; ++k) {
-        if (window_row_meets_column<Mask>(k, m1)) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const int i = j + COL1;
-                if (i >= 0 && i < V) {
-                    const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
-                    s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a1[k], r.at(k, i), c, 0, 0, 0);
-                    set[j] = true;
-                }
+// The order of work of one group of four window positions, as a compile-time list of jobs.  A job is
+// one filter column, or two evaluated together: a column COL lane-columns away from the output column
+// feeds only V - |COL| of the V sums, and a dependent MFMA can only follow after 12 cycles where an
+// independent one follows after 8, so the columns COL and COL + V, which feed complementary sums, are
+// interleaved row by row (from 14 filter columns on: the second column's operands cost registers, and
+// measured on 8192^2 pairing gains 7-10 % from 15x15 on and loses 2-10 % below 13x13).  The list follows
+// the two converging chains of systolic_rows: the columns a lane meets d lanes left of the output lane,
+// d = DL .. 1, each distance followed by a shift; the same from the right; then the owner's own columns.
+struct MfmaJob {
+    int m1, col1, m2, col2;   // filter column (0 .. M-1) and lane-column distance COL, first and second column
+    bool has2;
+    int chain;                // 0: sums arriving from the left, 1: from the right, 2: the output lane itself
+    bool shift, merge;        // after the job: shift the chain's sums one lane on / add them to the lane's own
+};
+
+template <int V, class Mask>
+struct MfmaPlan {
+    static constexpr bool kPair = Mask::kM >= 14;
+    static constexpr int kMaxJobs = 2 * Mask::kM;
+    struct List {
+        MfmaJob job[kMaxJobs];
+        int n;
+    };
+    static constexpr void add_group(List& l, int base, int lo, int hi, int chain)
+    {
+        const int ax = Mask::kAX;
+        if (kPair) {
+            for (int cc = 0; cc < V; ++cc) {
+                const int col1 = cc - (V - 1), col2 = col1 + V;   // -(V-1) .. 0 and 1 .. V (V itself never fits)
+                const int dx1 = col1 + base, dx2 = col2 + base;
+                const bool in1 = dx1 >= lo && dx1 <= hi, in2 = col2 < V && dx2 >= lo && dx2 <= hi;
+                if (in1 && in2) l.job[l.n++] = MfmaJob{ax + dx1, col1, ax + dx2, col2, true, chain, false, false};
+                else if (in1) l.job[l.n++] = MfmaJob{ax + dx1, col1, 0, 0, false, chain, false, false};
+                else if (in2) l.job[l.n++] = MfmaJob{ax + dx2, col2, 0, 0, false, chain, false, false};
+            }
+        } else {
+            for (int cc = 0; cc < 2 * V - 1; ++cc) {
+                const int col = cc - (V - 1), dx = col + base;
+                if (dx >= lo && dx <= hi) l.job[l.n++] = MfmaJob{ax + dx, col, 0, 0, false, chain, false, false};
             }
         }
-        if (HAS2 && window_row_meets_column<Mask>(k, m2)) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const int i = j + COL2;
-                if (i >= 0 && i < V) {
-                    const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
-                    s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a2[HAS2 ? k : 0], r.at(k, i), c, 0, 0, 0);
-                    set[j] = true;
-                }
-            }
+    }
+    static constexpr List make()
+    {
+        List l{};
+        constexpr int DL = (Mask::kLeft + V - 1) / V, DR = (Mask::kRight + V - 1) / V;
+        for (int d = DL; d >= 1; --d) {
+            add_group(l, -d * V, -Mask::kLeft, -1, 0);
+            l.job[l.n - 1].shift = true;
         }
+        if (DL > 0) l.job[l.n - 1].merge = true;
+        for (int d = DR; d >= 1; --d) {
+            add_group(l, d * V, 1, Mask::kRight, 1);
+            l.job[l.n - 1].shift = true;
+        }
+        if (DR > 0) l.job[l.n - 1].merge = true;
+        add_group(l, 0, -Mask::kLeft, Mask::kRight, 2);
+        return l;
     }
-}
+    static constexpr List list = make();
+};
 
-// The filter columns a lane meets at one distance from the output lane, taken in pairs (COL, COL + V):
-// IN(dx) says whether offset dx lies inside the filter on this side, BASE is the lane distance in
-// columns (dx = COL + BASE).
-template <int V, class Mask, int BASE, int LO, int HI, class Rows>
-__device__ __forceinline__ void column_group_mfma(const Rows& r, const float* tab_lane, v4f (&s)[V], bool (&set)[V])
-{
-    // Pairing costs registers (two columns of operands in flight): measured on 8192^2 it gains 7-10 %
-    // from 15x15 on and loses 2-10 % below 13x13.
-    constexpr bool PAIR = Mask::kM >= 14;
-    if constexpr (PAIR) {
-        static_for<V>([&](auto cc) __attribute__((always_inline)) {
-            constexpr int col1 = decltype(cc)::value - (V - 1), col2 = col1 + V;   // -(V-1) .. 0 and 1 .. V (V itself never fits)
-            constexpr int dx1 = col1 + BASE, dx2 = col2 + BASE;
-            constexpr bool in1 = dx1 >= LO && dx1 <= HI, in2 = col2 < V && dx2 >= LO && dx2 <= HI;
-            if constexpr (in1 && in2) column_products_mfma<V, Mask, dx1, col1, true, dx2, col2, Rows>(r, tab_lane, s, set);
-            else if constexpr (in1) column_products_mfma<V, Mask, dx1, col1, false, 0, 0, Rows>(r, tab_lane, s, set);
-            else if constexpr (in2) column_products_mfma<V, Mask, dx2, col2, false, 0, 0, Rows>(r, tab_lane, s, set);
-        });
-    } else {
-        static_for<2 * V - 1>([&](auto cc) __attribute__((always_inline)) {
-            constexpr int col = decltype(cc)::value - (V - 1), dx = col + BASE;
-            if constexpr (dx >= LO && dx <= HI) column_products_mfma<V, Mask, dx, col, false, 0, 0, Rows>(r, tab_lane, s, set);
-        });
-    }
-}
-
-// systolic_rows for fp32, P = 4, no incoming sums, with the products on the matrix cores: the same
-// two converging chains and the same shifts.
+// systolic_rows for fp32, P = 4, no incoming sums, with the products on the matrix cores: the same two
+// converging chains and the same shifts.  tab_lane = table + (lane % 4) * pitch.  The a operands of a job are
+// requested from LDS while the MFMAs of the job before it run (two sets of operand registers that
+// alternate; a job of two columns is split into two halves of the window rows so that the two sets together
+// are no larger than one job's operands): the LDS reads of the operands, 23 per filter column at 20x20,
+// otherwise cost 11 % of the launch.  Scheduling barriers keep that order: without them the compiler either
+// requests the whole table ahead and spills, or puts every read next to its use and waits for each; the
+// opaque zero in the table address keeps the reads of a job from being hoisted further.
 template <int V, class Mask, class Rows>
 __device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* tab_lane, float (&out)[4][V])
 {
     static_assert(Rows::kRows >= Mask::kN + 3, "register cache too small for the sliding window");
-    constexpr int DL = (Mask::kLeft + V - 1) / V;
-    constexpr int DR = (Mask::kRight + V - 1) / V;
-    v4f sum[V];
-    bool have[V];
+    typedef MfmaPlan<V, Mask> Plan;
+    constexpr int C = MfmaWeights<Mask>::kRows, CP = MfmaWeights<Mask>::kPitch;
+    constexpr int H = Plan::kPair ? 2 : 1;           // parts a job's window rows are requested in
+    constexpr int CH = (CP / 4 + H - 1) / H * 4;     // window rows per part: whole 16-byte pieces
+    constexpr int T = Plan::list.n * H;
+    v4f sum[V], sl[V], sr[V];
+    bool have[V], gl[V], gr[V];
 #pragma unroll
-    for (int j = 0; j < V; ++j) have[j] = false;
+    for (int j = 0; j < V; ++j) have[j] = gl[j] = gr[j] = false;
+    float a[2][2][CH];
 
-    if constexpr (DL > 0) {
-        v4f s[V];
-        bool got[V];
+    auto request = [&](auto uu) __attribute__((always_inline)) {
+        constexpr int u = decltype(uu)::value;
+        constexpr MfmaJob jb = Plan::list.job[u / H];
+        constexpr int k0 = (u % H) * CH;
+        const float* col = tab_lane + opaque_zero();
 #pragma unroll
-        for (int j = 0; j < V; ++j) got[j] = false;
-        static_for<DL>([&](auto dc) __attribute__((always_inline)) {
-            constexpr int d = DL - decltype(dc)::value;
-            column_group_mfma<V, Mask, -d * V, -Mask::kLeft, -1, Rows>(r, tab_lane, s, got);
+        for (int kk = 0; kk < CH; kk += 4) {
+            const int k = k0 + kk;
+            if (k < C) {
+                const v4f p1 = *reinterpret_cast<const v4f*>(col + jb.m1 * 4 * CP + k);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[u & 1][0][kk + e] = p1[e];
+                if (jb.has2) {
+                    const v4f p2 = *reinterpret_cast<const v4f*>(col + jb.m2 * 4 * CP + k);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[u & 1][1][kk + e] = p2[e];
+                }
+            }
+        }
+    };
+    auto products = [&](auto uu, v4f (&s)[V], bool (&set)[V]) __attribute__((always_inline)) {
+        constexpr int u = decltype(uu)::value;
+        constexpr MfmaJob jb = Plan::list.job[u / H];
+        constexpr int k0 = (u % H) * CH;
+#pragma unroll
+        for (int kk = 0; kk < CH; ++kk) {
+            const int k = k0 + kk;
+            if (k < C && window_row_meets_column<Mask>(k, jb.m1)) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const int i = j + jb.col1;
+                    if (i >= 0 && i < V) {
+                        const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                        s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u & 1][0][kk], r.at(k, i), c, 0, 0, 0);
+                        set[j] = true;
+                    }
+                }
+            }
+            if (k < C && jb.has2 && window_row_meets_column<Mask>(k, jb.m2)) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const int i = j + jb.col2;
+                    if (i >= 0 && i < V) {
+                        const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                        s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u & 1][1][kk], r.at(k, i), c, 0, 0, 0);
+                        set[j] = true;
+                    }
+                }
+            }
+        }
+    };
+
+    request(std::integral_constant<int, 0>{});
+    static_for<T>([&](auto uu) __attribute__((always_inline)) {
+        constexpr int u = decltype(uu)::value;
+        constexpr MfmaJob jb = Plan::list.job[u / H];
+        if constexpr (u + 1 < T) request(std::integral_constant<int, u + 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (jb.chain == 0) products(uu, sl, gl);
+        else if constexpr (jb.chain == 1) products(uu, sr, gr);
+        else products(uu, sum, have);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (u % H == H - 1 && jb.shift) {
 #pragma unroll
             for (int j = 0; j < V; ++j)
-                if (got[j]) {
+                if (jb.chain == 0 ? gl[j] : gr[j]) {
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) s[j][p] = shift_up(s[j][p]);
+                    for (int p = 0; p < 4; ++p) {
+                        if constexpr (jb.chain == 0) sl[j][p] = shift_up(sl[j][p]);
+                        else sr[j][p] = shift_down(sr[j][p]);
+                    }
                 }
-        });
-#pragma unroll
-        for (int j = 0; j < V; ++j)
-            if (got[j]) {
-                sum[j] = have[j] ? sum[j] + s[j] : s[j];
-                have[j] = true;
-            }
-    }
-    if constexpr (DR > 0) {
-        v4f s[V];
-        bool got[V];
-#pragma unroll
-        for (int j = 0; j < V; ++j) got[j] = false;
-        static_for<DR>([&](auto dc) __attribute__((always_inline)) {
-            constexpr int d = DR - decltype(dc)::value;
-            column_group_mfma<V, Mask, d * V, 1, Mask::kRight, Rows>(r, tab_lane, s, got);
+        }
+        if constexpr (u % H == H - 1 && jb.merge) {
 #pragma unroll
             for (int j = 0; j < V; ++j)
-                if (got[j]) {
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) s[j][p] = shift_down(s[j][p]);
+                if (jb.chain == 0 ? gl[j] : gr[j]) {
+                    const v4f s = jb.chain == 0 ? sl[j] : sr[j];
+                    sum[j] = have[j] ? sum[j] + s : s;
+                    have[j] = true;
                 }
-        });
-#pragma unroll
-        for (int j = 0; j < V; ++j)
-            if (got[j]) {
-                sum[j] = have[j] ? sum[j] + s[j] : s[j];
-                have[j] = true;
-            }
-    }
-    column_group_mfma<V, Mask, 0, -Mask::kLeft, Mask::kRight, Rows>(r, tab_lane, sum, have);
+        }
+    });
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
 
     typedef Args2D<T, Mask::kNW> Args;
     const ConstPtr<T> wts = kernarg_member<T>(offsetof(Args, w));
-    __shared__ float mfma_tab[ENGINE == 1 ? MfmaWeights<Mask>::kWords : 1];
+    __shared__ __attribute__((aligned(16))) float mfma_tab[ENGINE == 1 ? MfmaWeights<Mask>::kWords : 4];
     if constexpr (ENGINE == 1) {
         fill_mfma_weights<Mask>(wts, mfma_tab);      // before any wave leaves: every thread helps and waits
         __syncthreads();
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kBlock) void ssam2d_kernel(const Args2D<T, Mask::kN
 
                     T acc[P][V];
                     if constexpr (ENGINE == 1)
-                        systolic_rows_mfma<V, Mask>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, mfma_tab + (lane & 3), acc);
+                        systolic_rows_mfma<V, Mask>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, mfma_tab + (lane & 3) * MfmaWeights<Mask>::kPitch, acc);
                     else
                         systolic_rows<T, V, P, Mask, false>(RowPair<T, V, KEEP, P>{keep, fresh[cur]}, wts, acc, acc);
                     store_rows(y, acc);
