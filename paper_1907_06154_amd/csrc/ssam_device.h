@@ -450,46 +450,30 @@ __host__ __device__ constexpr bool window_row_meets_column(int k, int m)
     return false;
 }
 
-// The order of work of one group of four window positions, as a compile-time list of jobs.  A job is
-// one filter column, or two evaluated together: a column COL lane-columns away from the output column
-// feeds only V - |COL| of the V sums, and a dependent MFMA can only follow after 12 cycles where an
-// independent one follows after 8, so the columns COL and COL + V, which feed complementary sums, are
-// interleaved row by row (from 14 filter columns on: the second column's operands cost registers, and
-// measured on 8192^2 pairing gains 7-10 % from 15x15 on and loses 2-10 % below 13x13).  The list follows
-// the two converging chains of systolic_rows: the columns a lane meets d lanes left of the output lane,
-// d = DL .. 1, each distance followed by a shift; the same from the right; then the owner's own columns.
+// The order of work of one group of four window positions, as a compile-time list of jobs, one per filter
+// column a lane meets at one lane-column distance COL from the output column (such a column feeds V - |COL|
+// of the V sums).  The list follows the two converging chains of systolic_rows: the columns a lane meets d
+// lanes left of the output lane, d = DL .. 1, each distance followed by a shift; the same from the right;
+// then the owner's own columns.
 struct MfmaJob {
-    int m1, col1, m2, col2;   // filter column (0 .. M-1) and lane-column distance COL, first and second column
-    bool has2;
-    int chain;                // 0: sums arriving from the left, 1: from the right, 2: the output lane itself
-    bool shift, merge;        // after the job: shift the chain's sums one lane on / add them to the lane's own
+    int m, col;          // filter column (0 .. M-1) and lane-column distance COL
+    int chain;           // 0: sums arriving from the left, 1: from the right, 2: the output lane itself
+    bool shift, merge;   // after the job: shift the chain's sums one lane on / add them to the lane's own
 };
 
 template <int V, class Mask>
 struct MfmaPlan {
-    static constexpr bool kPair = Mask::kM >= 14;
     static constexpr int kMaxJobs = 2 * Mask::kM;
     struct List {
         MfmaJob job[kMaxJobs];
         int n;
     };
+    // the filter columns dx = COL + base, lo <= dx <= hi, a lane meets at one distance from the output lane
     static constexpr void add_group(List& l, int base, int lo, int hi, int chain)
     {
-        const int ax = Mask::kAX;
-        if (kPair) {
-            for (int cc = 0; cc < V; ++cc) {
-                const int col1 = cc - (V - 1), col2 = col1 + V;   // -(V-1) .. 0 and 1 .. V (V itself never fits)
-                const int dx1 = col1 + base, dx2 = col2 + base;
-                const bool in1 = dx1 >= lo && dx1 <= hi, in2 = col2 < V && dx2 >= lo && dx2 <= hi;
-                if (in1 && in2) l.job[l.n++] = MfmaJob{ax + dx1, col1, ax + dx2, col2, true, chain, false, false};
-                else if (in1) l.job[l.n++] = MfmaJob{ax + dx1, col1, 0, 0, false, chain, false, false};
-                else if (in2) l.job[l.n++] = MfmaJob{ax + dx2, col2, 0, 0, false, chain, false, false};
-            }
-        } else {
-            for (int cc = 0; cc < 2 * V - 1; ++cc) {
-                const int col = cc - (V - 1), dx = col + base;
-                if (dx >= lo && dx <= hi) l.job[l.n++] = MfmaJob{ax + dx, col, 0, 0, false, chain, false, false};
-            }
+        for (int col = -(V - 1); col <= V - 1; ++col) {
+            const int dx = col + base;
+            if (dx >= lo && dx <= hi) l.job[l.n++] = MfmaJob{Mask::kAX + dx, col, chain, false, false};
         }
     }
     static constexpr List make()
@@ -513,73 +497,49 @@ struct MfmaPlan {
 };
 
 // systolic_rows for fp32, P = 4, no incoming sums, with the products on the matrix cores: the same two
-// converging chains and the same shifts.  tab_lane = table + (lane % 4) * pitch.  The a operands of a job are
-// requested from LDS while the MFMAs of the job before it run (two sets of operand registers that
-// alternate; a job of two columns is split into two halves of the window rows so that the two sets together
-// are no larger than one job's operands): the LDS reads of the operands, 23 per filter column at 20x20,
-// otherwise cost 11 % of the launch.  Scheduling barriers keep that order: without them the compiler either
-// requests the whole table ahead and spills, or puts every read next to its use and waits for each; the
-// opaque zero in the table address keeps the reads of a job from being hoisted further.
+// converging chains and the same shifts.  tab_lane = table + (lane % 4) * pitch.  The a operands of a job
+// are requested from LDS while the MFMAs of the job before it run (two sets of operand registers that
+// alternate): waiting for them at every filter column otherwise costs 2-6 % of the launch.  Scheduling
+// barriers keep that order: without them the compiler either requests the whole table ahead and spills, or
+// puts every read next to its use and waits for each; the opaque zero in the table address keeps the reads
+// of a job from being hoisted further.  (Evaluating the columns COL and COL + V, which feed complementary
+// sums, interleaved -- so that no MFMA follows one it depends on -- measured the same as this order.)
 template <int V, class Mask, class Rows>
 __device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* tab_lane, float (&out)[4][V])
 {
     static_assert(Rows::kRows >= Mask::kN + 3, "register cache too small for the sliding window");
     typedef MfmaPlan<V, Mask> Plan;
     constexpr int C = MfmaWeights<Mask>::kRows, CP = MfmaWeights<Mask>::kPitch;
-    constexpr int H = Plan::kPair ? 2 : 1;           // parts a job's window rows are requested in
-    constexpr int CH = (CP / 4 + H - 1) / H * 4;     // window rows per part: whole 16-byte pieces
-    constexpr int T = Plan::list.n * H;
+    constexpr int T = Plan::list.n;
     v4f sum[V], sl[V], sr[V];
     bool have[V], gl[V], gr[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) have[j] = gl[j] = gr[j] = false;
-    float a[2][2][CH];
+    float a[2][CP];
 
-    auto request = [&](auto uu) __attribute__((always_inline)) {
-        constexpr int u = decltype(uu)::value;
-        constexpr MfmaJob jb = Plan::list.job[u / H];
-        constexpr int k0 = (u % H) * CH;
+    auto request = [&](auto tt) __attribute__((always_inline)) {
+        constexpr int t = decltype(tt)::value;
+        constexpr MfmaJob jb = Plan::list.job[t];
         const float* col = tab_lane + opaque_zero();
 #pragma unroll
-        for (int kk = 0; kk < CH; kk += 4) {
-            const int k = k0 + kk;
-            if (k < C) {
-                const v4f p1 = *reinterpret_cast<const v4f*>(col + jb.m1 * 4 * CP + k);
+        for (int k = 0; k < CP; k += 4) {
+            const v4f piece = *reinterpret_cast<const v4f*>(col + jb.m * 4 * CP + k);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[u & 1][0][kk + e] = p1[e];
-                if (jb.has2) {
-                    const v4f p2 = *reinterpret_cast<const v4f*>(col + jb.m2 * 4 * CP + k);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) a[u & 1][1][kk + e] = p2[e];
-                }
-            }
+            for (int e = 0; e < 4; ++e) a[t & 1][k + e] = piece[e];
         }
     };
-    auto products = [&](auto uu, v4f (&s)[V], bool (&set)[V]) __attribute__((always_inline)) {
-        constexpr int u = decltype(uu)::value;
-        constexpr MfmaJob jb = Plan::list.job[u / H];
-        constexpr int k0 = (u % H) * CH;
+    auto products = [&](auto tt, v4f (&s)[V], bool (&set)[V]) __attribute__((always_inline)) {
+        constexpr int t = decltype(tt)::value;
+        constexpr MfmaJob jb = Plan::list.job[t];
 #pragma unroll
-        for (int kk = 0; kk < CH; ++kk) {
-            const int k = k0 + kk;
-            if (k < C && window_row_meets_column<Mask>(k, jb.m1)) {
+        for (int k = 0; k < C; ++k) {
+            if (window_row_meets_column<Mask>(k, jb.m)) {
 #pragma unroll
                 for (int j = 0; j < V; ++j) {
-                    const int i = j + jb.col1;
+                    const int i = j + jb.col;
                     if (i >= 0 && i < V) {
                         const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
-                        s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u & 1][0][kk], r.at(k, i), c, 0, 0, 0);
-                        set[j] = true;
-                    }
-                }
-            }
-            if (k < C && jb.has2 && window_row_meets_column<Mask>(k, jb.m2)) {
-#pragma unroll
-                for (int j = 0; j < V; ++j) {
-                    const int i = j + jb.col2;
-                    if (i >= 0 && i < V) {
-                        const v4f c = set[j] ? s[j] : v4f{0.0f, 0.0f, 0.0f, 0.0f};
-                        s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u & 1][1][kk], r.at(k, i), c, 0, 0, 0);
+                        s[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[t & 1][k], r.at(k, i), c, 0, 0, 0);
                         set[j] = true;
                     }
                 }
@@ -588,16 +548,16 @@ __device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* t
     };
 
     request(std::integral_constant<int, 0>{});
-    static_for<T>([&](auto uu) __attribute__((always_inline)) {
-        constexpr int u = decltype(uu)::value;
-        constexpr MfmaJob jb = Plan::list.job[u / H];
-        if constexpr (u + 1 < T) request(std::integral_constant<int, u + 1>{});
+    static_for<T>([&](auto tt) __attribute__((always_inline)) {
+        constexpr int t = decltype(tt)::value;
+        constexpr MfmaJob jb = Plan::list.job[t];
+        if constexpr (t + 1 < T) request(std::integral_constant<int, t + 1>{});
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (jb.chain == 0) products(uu, sl, gl);
-        else if constexpr (jb.chain == 1) products(uu, sr, gr);
-        else products(uu, sum, have);
+        if constexpr (jb.chain == 0) products(tt, sl, gl);
+        else if constexpr (jb.chain == 1) products(tt, sr, gr);
+        else products(tt, sum, have);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (u % H == H - 1 && jb.shift) {
+        if constexpr (jb.shift) {
 #pragma unroll
             for (int j = 0; j < V; ++j)
                 if (jb.chain == 0 ? gl[j] : gr[j]) {
@@ -608,7 +568,7 @@ __device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* t
                     }
                 }
         }
-        if constexpr (u % H == H - 1 && jb.merge) {
+        if constexpr (jb.merge) {
 #pragma unroll
             for (int j = 0; j < V; ++j)
                 if (jb.chain == 0 ? gl[j] : gr[j]) {
