@@ -25,6 +25,9 @@ def cases():
     f3 = wl.uniform_field((4, 5, 6), -1.0, 1.0, 6, np.float64)
     yield "faces_edges_4x5x6_f64_zero_3sweeps", oracle.iterate(f3, wl.seeded_coefficients(wl.mask_faces_edges(), 62, np.float64), 3)
     yield "star_r4_4x5x6_f64_clamp", oracle.stencil(f3, wl.seeded_symmetric_star(4, 3, 70, np.float64), "clamp")
+    filt3 = wl.uniform_field((2, 3, 4), -1.0, 1.0, 71, np.float64)      # even and odd extents, anchor off the centre
+    yield "conv3d_4x3x2_anchor_3_0_1_4x5x6_f64_zero", oracle.conv3d(f3, filt3, "zero", anchor=(3, 0, 1))
+    yield "scan_37_f32", oracle.scan(wl.uniform_field((37,), -1.0, 1.0, 72, np.float32))
 
 
 def render():
