@@ -562,10 +562,14 @@ def tune(ssam, wl, torch, args) -> int:
         a = wl.uniform_field_on("cuda", c.shape, c.field_range[0], c.field_range[1], c.field_seed, c.dtype)
         b = torch.empty_like(a)
         sweeps = 1 if c.kind == "conv2d" else min(c.steps, 24)
+        # --cold: a single-pass case reads a different copy of its input at every launch
+        inputs = [a] + [a.clone() for _ in range(COLD_COPIES - 1)] if args.cold and c.kind == "conv2d" else [a]
+        turn = [0]
 
         def run():
             if c.kind == "conv2d":
-                ssam.ssam_conv2d(a, c.coef, c.boundary, d_out=b)
+                turn[0] = (turn[0] + 1) % len(inputs)
+                ssam.ssam_conv2d(inputs[turn[0]], c.coef, c.boundary, d_out=b)
             else:
                 ssam.ssam_stencil_iterate(a, b, case_coef(c), sweeps, c.boundary)
 
@@ -580,7 +584,7 @@ def tune(ssam, wl, torch, args) -> int:
             print(f"{c.name:26s} {knobs}  {ms * 1e3:8.1f} us {gpt:7.1f} GStencil/s {gpt * 2 * np.dtype(c.dtype).itemsize:7.0f} GB/s", flush=True)
         for k in keys:
             ssam.ssam_set_tuning(k, -1)
-        del a, b
+        del a, b, inputs
         torch.cuda.empty_cache()
     return 0
 
@@ -601,6 +605,7 @@ def main() -> int:
     ap.add_argument("--headline-only", action="store_true", help="default workload: skip configurations 1, 3, 4, 5")
     ap.add_argument("--variant", type=int, default=-1,
                     help="tuning variant for the whole run (e.g. 5: vector-unit instances of the matrix-core filters)")
+    ap.add_argument("--cold", action="store_true", help="--tune: rotate the input of single-pass cases among 4 copies")
     ap.add_argument("--tune", default=None, help='"knob=v1,v2;knob2=..." : time the selected cases under tuning overrides')
     args = ap.parse_args()
 
