@@ -207,8 +207,8 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
     // Filters of 7x7 and more are limited by instruction issue: they use every lane they can and balance the
     // tile count; bandwidth-bound ones keep strips line-aligned and tiles short.  (Measured on 8192^2 fp32 with
     // the input cold in the memory-side cache: 6x6 124 -> 104 us, 11x3 123 -> 102, 3x11 120 -> 110 when planned
-    // as bandwidth-bound; 7x7 the same either way; 8x8 and up 3-4 % slower.  On an input that is resident in that
-    // cache the balanced plan is the faster one up to 6x6: 97 against 107 us.)
+    // as bandwidth-bound, and no slower on an input resident in that cache; 7x7 the same either way; 8x8 and up
+    // 3-4 % slower.)
     constexpr bool kArith = Mask::kNW >= 40;
     plan_strips(pr.W, V, HL, HR, tu.valid_lanes, &g, !kArith);
     g.P = P;
