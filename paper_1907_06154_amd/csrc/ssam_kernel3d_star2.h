@@ -7,8 +7,8 @@
 //   level 1  the first sweep on the wave's P rows widened by one row above and below and one COLUMN on
 //            either side of every lane's V columns: (P + 2) x (V + 2) points per lane, the output planes
 //            in flight along z as usual.  The widening rows are recomputed by the neighbouring wave and
-//            the widening columns by the neighbouring lane; that redundancy (3x the first sweep for fp64,
-//            2.25x for fp32) is arithmetic the 7-point star has to spare -- one sweep keeps 12 % of the
+//            the widening columns by the neighbouring lane; that redundancy (3x the first sweep at P = 4, V = 2 and
+//            at P = 2, V = 4) is arithmetic the 7-point star has to spare -- one sweep keeps 12 % of the
 //            vector issue slots busy -- and in exchange no first-sweep value ever crosses a lane or a wave,
 //            all 64 lanes store, and nothing but the grid itself goes through memory;
 //   level 2  the second sweep on the P x V points the lane owns, fed by the first-sweep plane that has just
