@@ -145,7 +145,7 @@ def summarize(prefix: str, out_md: str, title: str, bench_args: str) -> None:
 def sweeps_of(kernel: str) -> int:
     if "ssam2d_fused" in kernel:
         return int(re.search(r">, (\d+), \d+>$", kernel).group(1))
-    return 2 if "ssam3d_fused" in kernel else 1
+    return 2 if "ssam3d_fused" in kernel or "ssam3d_star2" in kernel else 1
 
 
 def sq(dirs, out_md: str) -> None:
