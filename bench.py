@@ -21,7 +21,10 @@ configuration-2 case compared in this process with the field the CPU oracle comp
 
 Other workloads: --workload config1 .. config5, filter_sweep, table3 (a step is then the whole
 configuration: every case, all its sweeps), scan.  --tune "<knob>=v1,v2;<knob2>=..." times the
-selected cases under every combination of tuning overrides (ssam_set_tuning) instead.
+selected cases under every combination of tuning overrides (ssam_set_tuning) instead, one after the
+other in this process (the clock differs between processes and boxes by several per cent, so variants
+are only comparable within one run); with --cold the single-pass cases rotate their input as the
+default workload does.  The two grids of an iterated case are carved from one allocation, back to back.
 """
 from __future__ import annotations
 
