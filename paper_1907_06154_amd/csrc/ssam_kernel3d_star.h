@@ -26,10 +26,11 @@
 //     the younger requests that may stay outstanding is enough), then one barrier.
 //   - Boundary rule in the fetch.  Zero padding: a piece outside the grid is loaded from 16 zero
 //     bytes the library keeps in device memory (so every lane issues every load and the request
-//     counts are the same in all waves).  Clamp: row and plane indices are clamped; blocks whose
-//     tile reaches past the grid in x or y -- pieces left or right of the grid take the edge
-//     column of their row, which no plain load delivers -- stage through registers instead (one
-//     plane ahead).
+//     counts are the same in all waves).  Clamp: row and plane indices are clamped in the fetch (a
+//     replicated row or plane is a plain load); columns left or right of the grid take the edge
+//     column of their row, which no plain load delivers, so blocks at the left or right edge of the
+//     grid replace those pieces when they READ the staged plane: one more broadcast read of the
+//     row's edge piece, only in those blocks.
 // Requirements (the launcher falls back to ssam3d_lds_kernel otherwise): W a multiple of V and
 // both base pointers 16-byte aligned.
 #pragma once
@@ -151,7 +152,6 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     unsigned off[NCH];      // byte offset of the piece inside a plane (row and column clamped into the grid);
                             // 32 bits: the launcher sends larger planes to the other kernel
     unsigned inb = 0;       // bit i: piece i exists and lies inside the grid in x and y
-    unsigned lft = 0, rgt = 0;   // bit i: piece i lies left / right of the grid
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int f = i * NTHR + tid;
@@ -160,8 +160,6 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         const int yy = min(max(y, 0), H - 1), xx = min(max(x, 0), W - V);
         off[i] = (unsigned)(((size_t)yy * rowst + xx) * sizeof(T));
         inb |= (f < TOTAL && y >= 0 && y < H && x >= 0 && x < W) ? 1u << i : 0u;
-        lft |= (f < TOTAL && x < 0) ? 1u << i : 0u;
-        rgt |= (f < TOTAL && x >= W) ? 1u << i : 0u;
     }
 
     T acc[NZ][P][V];
@@ -177,8 +175,49 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int edge_l = (wave * P) * RS;              // the row's first piece; HC pieces of left halo
     const int edge_r = (wave * P) * RS + HC + kWave; // HC pieces of right halo
 
+    // Clamp rule at the left / right edge of the grid (block-uniform): the halo pieces, and the pieces of lanes
+    // beyond the last column, are the row's edge column repeated.
+    const bool clamp_l = clamp && x0 == 0;                  // the left halo pieces lie outside the grid
+    const bool clamp_r = clamp && x0 + kWave * V > W;       // so do the pieces of the lanes from column W on
+    // right halo pieces 1 .. right_in lie inside the grid, the others outside
+    const int right_in = clamp ? min(max((W - x0 - kWave * V) / V, 0), HC) : HC;
+    const int last_piece = (wave * P) * RS + HC + (W - x0) / V - 1;   // the piece that ends in column W-1 (when one of the above is outside)
+    const bool beyond = xc >= W;
+    auto splat = [](T x) __attribute__((always_inline)) {
+        vec_t r;
+#pragma unroll
+        for (int j = 0; j < V; ++j) r[j] = x;
+        return r;
+    };
+    // row `k` of the wave's window in staged plane `st`: the lane's own piece, and halo piece h (1 = nearest).
+    // EX (compile time): the block lies at the left or right edge of the grid under the clamp rule; every other
+    // block reads the staged pieces as they are and pays nothing for the rule.
+    auto own_piece = [&](auto ex, const vec_t* st, int k) __attribute__((always_inline)) {
+        vec_t v = st[own + k * RS];
+        if constexpr (decltype(ex)::value) {
+            if (clamp_r) {
+                const vec_t e = splat(st[last_piece + k * RS][V - 1]);
+#pragma unroll
+                for (int j = 0; j < V; ++j) v[j] = beyond ? e[j] : v[j];
+            }
+        }
+        return v;
+    };
+    auto left_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        if constexpr (decltype(ex)::value) {
+            if (clamp_l) return splat(st[edge_l + k * RS + HC][0]);
+        }
+        return st[edge_l + k * RS + (HC - h)];   // same address in every lane: a broadcast
+    };
+    auto right_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        if constexpr (decltype(ex)::value) {
+            if (h > right_in) return splat(st[last_piece + k * RS][V - 1]);
+        }
+        return st[edge_r + k * RS + (h - 1)];
+    };
+
     // one step of the march: the staged plane `st` is input plane zin
-    auto step = [&](const vec_t* st, int zin) __attribute__((always_inline)) {
+    auto step = [&](auto ex, const vec_t* st, int zin) __attribute__((always_inline)) {
         if constexpr (BUDGET == 1) {
             T sum[P][V];       // in-plane sums, seeded with the plane above's partial sums
             // -- per window: z taps and the centre tap (in-flight plane s takes dz = R - s from this
@@ -188,7 +227,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 T xs[(2 * HC + 1) * V];     // columns -HC*V .. (HC+1)*V - 1 relative to the lane's first
-                const vec_t v = st[own + (p + R) * RS];
+                const vec_t v = own_piece(ex, st, p + R);
 #pragma unroll
                 for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
                 const T* cen = &xs[HC * V];
@@ -206,8 +245,8 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
                 for (int j = 0; j < V; ++j) acc[NZ - 1][p][j] = cen[j] * wts[0];
 #pragma unroll
                 for (int h = 1; h <= HC; ++h) {
-                    const vec_t el = st[edge_l + (p + R) * RS + (HC - h)];   // same address in every lane: a broadcast
-                    const vec_t er = st[edge_r + (p + R) * RS + (h - 1)];
+                    const vec_t el = left_piece(ex, st, p + R, h);
+                    const vec_t er = right_piece(ex, st, p + R, h);
 #pragma unroll
                     for (int j = 0; j < V; ++j) {
                         xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
@@ -225,7 +264,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             // -- y taps: every staged row of the wave's window
 #pragma unroll
             for (int k = 0; k < C; ++k) {
-                const vec_t v = st[own + k * RS];
+                const vec_t v = own_piece(ex, st, k);
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     const int dy = k - R - p;
@@ -255,13 +294,13 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
             for (int k = 0; k < C; ++k) {
                 T xs[(2 * HC + 1) * V];
-                const vec_t v = st[own + k * RS];
+                const vec_t v = own_piece(ex, st, k);
 #pragma unroll
                 for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
 #pragma unroll
                 for (int h = 1; h <= HC; ++h) {
-                    const vec_t el = st[edge_l + k * RS + (HC - h)];
-                    const vec_t er = st[edge_r + k * RS + (h - 1)];
+                    const vec_t el = left_piece(ex, st, k, h);
+                    const vec_t er = right_piece(ex, st, k, h);
 #pragma unroll
                     for (int j = 0; j < V; ++j) {
                         xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
@@ -310,25 +349,26 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         }
     };
 
-    if (inside_xy || !clamp) {
-        // ---- planes straight into LDS, PF steps ahead --------------------------------------------
-        const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
-        auto request = [&](int z, int b) __attribute__((always_inline)) {
-            const bool plane_in = clamp || (z >= 0 && z < D);                     // block-uniform
-            const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
-            const unsigned keep = plane_in ? ~0u : 0u;
+    // ---- planes straight into LDS, PF steps ahead --------------------------------------------
+    const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
+    auto request = [&](int z, int b) __attribute__((always_inline)) {
+        const bool plane_in = clamp || (z >= 0 && z < D);                     // block-uniform
+        const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
+        const unsigned keep = plane_in ? ~0u : 0u;
 #pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const char* src = pz + (off[i] & keep);
-                if (!inside_xy || (i + 1) * NTHR > TOTAL) src = (inb >> i) & 1u ? src : zero_src;
-                load16_to_lds(src, &stage[b][i * NTHR + wave * kWave]);
-            }
-        };
-        // a wave that stores all P rows issues P stores per step once output planes complete (step 2R on)
-        const bool full_rows = y0 + P <= H;
+        for (int i = 0; i < NCH; ++i) {
+            const char* src = pz + (off[i] & keep);
+            // zero padding: pieces outside the grid are zeros; clamp: every offset is already clamped into the grid
+            if (!clamp && (!inside_xy || (i + 1) * NTHR > TOTAL)) src = (inb >> i) & 1u ? src : zero_src;
+            load16_to_lds(src, &stage[b][i * NTHR + wave * kWave]);
+        }
+    };
+    // a wave that stores all P rows issues P stores per step once output planes complete (step 2R on)
+    const bool full_rows = y0 + P <= H;
 #pragma unroll
-        for (int k = 0; k < PF; ++k)
-            if (k < nt) request(z0 - R + k, k);
+    for (int k = 0; k < PF; ++k)
+        if (k < nt) request(z0 - R + k, k);
+    auto march = [&](auto ex) __attribute__((always_inline)) {
         int b = 0;
         for (int t = 0; t < nt; ++t) {
             // Requests younger than those of plane t (issued at the start of step t - PF): the stores of
@@ -343,39 +383,12 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             // buffer (t + PF) % NBUF held plane t - 1, which every wave has finished reading
             if (t + PF < nt) request(z0 - R + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
             asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it
-            step(stage[b], z0 - R + t);
+            step(ex, stage[b], z0 - R + t);
             b = b + 1 == NBUF ? 0 : b + 1;
         }
-    } else {
-        // ---- clamp rule, tile reaching past the grid in x or y: staged through registers ------
-        auto fetch = [&](int z, vec_t (&g)[NCH]) __attribute__((always_inline)) {
-            const char* pz = reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane);
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) g[i] = *reinterpret_cast<const vec_t*>(pz + off[i]);
-        };
-        auto stash = [&](int b, const vec_t (&g)[NCH]) __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                vec_t v = g[i];
-                const T first = v[0], last = v[V - 1];
-                const unsigned lm = (lft >> i) & 1u ? ~0u : 0u, rm = (rgt >> i) & 1u ? ~0u : 0u;
-#pragma unroll
-                for (int e = 0; e < V; ++e) v[e] = pick(pick(v[e], first, lm), last, rm);
-                stage[b][i * NTHR + tid] = v;
-            }
-        };
-        vec_t g[NCH];
-        fetch(z0 - R, g);
-        stash(0, g);
-        __syncthreads();
-        for (int t = 0; t < nt; ++t) {
-            const int b = t & 1;
-            if (t + 1 < nt) fetch(z0 - R + t + 1, g);
-            step(stage[b], z0 - R + t);
-            if (t + 1 < nt) stash(b ^ 1, g);
-            __syncthreads();
-        }
-    }
+    };
+    if (clamp_l || clamp_r || right_in < HC) march(std::true_type{});   // block-uniform
+    else march(std::false_type{});
 }
 
 // Fallback of a shape that has no other compiled instance: the dispatcher then takes the direct kernel.
