@@ -100,6 +100,73 @@ __device__ __forceinline__ void load16_to_lds(const void* src, void* lds_base)
 // Sixteen zero bytes: what a piece outside the grid is loaded from under zero padding.
 static __device__ __align__(16) const unsigned kZeroPiece[4] = {0u, 0u, 0u, 0u};
 
+// What one thread of a block fetches of every staged plane.  The staged tile is ROWS rows of RS = 64 + 2*HC
+// 16-byte pieces (HC halo pieces on either side of the strip's 64), split evenly over the block's NTHR threads:
+// piece f = i*NTHR + tid of the tile is row f / RS, piece f % RS of that row, so a wave's 64 loads of one
+// round are 64 consecutive pieces.  The pieces are the same for every plane: offsets are computed once.
+template <typename T, int ROWS, int HC, int NTHR>
+struct PlaneFetch {
+    static constexpr int V = 16 / (int)sizeof(T);
+    static constexpr int RS = kWave + 2 * HC;
+    static constexpr int TOTAL = ROWS * RS;
+    static constexpr int NCH = (TOTAL + NTHR - 1) / NTHR;   // pieces one thread fetches per plane
+    static constexpr int SLOTS = NCH * NTHR;                // LDS pieces per buffer (the last few are padding)
+    unsigned off[NCH];   // byte offset of the piece inside a plane, row and column clamped into the grid (32 bits:
+                         // the launcher sends larger planes to another kernel)
+    unsigned inb;        // bit i: piece i exists and lies inside the grid in x and y
+
+    // x0: first column of the strip; y_first: grid row of the tile's first row
+    __device__ __forceinline__ void plan(int tid, int x0, int y_first, int W, int H, size_t rowst)
+    {
+        inb = 0;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int f = i * NTHR + tid;
+            const int row = f / RS, c = f - row * RS;
+            const int y = y_first + row, x = x0 + (c - HC) * V;
+            const int yy = min(max(y, 0), H - 1), xx = min(max(x, 0), W - V);
+            off[i] = (unsigned)(((size_t)yy * rowst + xx) * sizeof(T));
+            inb |= (f < TOTAL && y >= 0 && y < H && x >= 0 && x < W) ? 1u << i : 0u;
+        }
+    }
+
+    // Requests plane z of `in` into `buf` (SLOTS pieces of LDS), straight from global memory.  Zero padding:
+    // pieces and planes outside the grid come from kZeroPiece, so every lane issues every load and the request
+    // counts agree in all waves.  Clamp: every offset is already clamped into the grid, and so is z.
+    // inside_xy (block-uniform): every piece of the tile lies inside the grid in x and y.
+    template <class Vec>
+    __device__ __forceinline__ void request(const T* in, size_t plane, int z, int D, bool clamp, bool inside_xy, Vec* buf,
+                                            int wave) const
+    {
+        const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
+        const bool plane_in = clamp || (z >= 0 && z < D);                     // block-uniform
+        const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
+        const unsigned keep = plane_in ? ~0u : 0u;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const char* src = pz + (off[i] & keep);
+            if (!clamp && (!inside_xy || (i + 1) * NTHR > TOTAL)) src = (inb >> i) & 1u ? src : zero_src;
+            load16_to_lds(src, &buf[i * NTHR + wave * kWave]);
+        }
+    }
+};
+
+// Requests of a wave that are younger than the loads of the plane used at step t, which were issued at the
+// start of step t - PF: the stores of steps t-PF .. t-1 (P per step from step `first_store` on, for a wave
+// that stores all its rows) and the loads of planes t+1 .. t+PF-1 (NCH each).  Requests complete in order, so
+// waiting until at most this many are outstanding means plane t has landed.
+template <int PF, int NCH, int P>
+__device__ __forceinline__ int younger_requests(int t, int nt, bool full_rows, int first_store)
+{
+    int younger = 0;
+#pragma unroll
+    for (int k = 1; k <= PF; ++k) {
+        if (k < PF && t + k < nt) younger += NCH;
+        if (full_rows && t - k >= first_store) younger += P;
+    }
+    return younger;
+}
+
 template <typename T, int P, int NW, int R, int BUDGET, int NBUF, int NT>
 __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) void ssam3d_star_kernel(
     const Args3D<T, SliceMask<R, R, R, BUDGET, 0>::kNW> a)
@@ -110,13 +177,10 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     typedef typename Piece16<T>::type vec_t;
     constexpr int NZ = 2 * R + 1;
     constexpr int HC = (R + V - 1) / V;        // halo pieces on each side of a staged row
-    constexpr int RS = kWave + 2 * HC;         // pieces per staged row
     constexpr int C = P + 2 * R;               // rows one wave evaluates from
-    constexpr int CB = NW * P + 2 * R;         // rows the block stages per plane
-    constexpr int TOTAL = CB * RS;             // pieces per staged plane
     constexpr int NTHR = NW * kWave;
-    constexpr int NCH = (TOTAL + NTHR - 1) / NTHR;   // pieces one thread fetches per plane
-    constexpr int SLOTS = NCH * NTHR;          // LDS pieces per buffer (the last few are padding)
+    typedef PlaneFetch<T, NW * P + 2 * R, HC, NTHR> Fetch;   // the block stages NW*P + 2R rows per plane
+    constexpr int RS = Fetch::RS, NCH = Fetch::NCH, SLOTS = Fetch::SLOTS;
     constexpr bool NT_STORE = (NT & kStreamStores) != 0;
     static_assert((PF - 1) * NCH + PF * P <= 30, "request count beyond what the wait encodes");
 
@@ -148,19 +212,8 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     // block-uniform: every staged piece lies inside the grid in x and y
     const bool inside_xy = x0 - HC * V >= 0 && x0 + (kWave + HC) * V <= W && yb0 - R >= 0 && yb0 + NW * P + R <= H;
 
-    // ---- this thread's pieces of the staged plane (the same for every plane) ----------------------
-    unsigned off[NCH];      // byte offset of the piece inside a plane (row and column clamped into the grid);
-                            // 32 bits: the launcher sends larger planes to the other kernel
-    unsigned inb = 0;       // bit i: piece i exists and lies inside the grid in x and y
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int f = i * NTHR + tid;
-        const int row = f / RS, c = f - row * RS;
-        const int y = yb0 - R + row, x = x0 + (c - HC) * V;
-        const int yy = min(max(y, 0), H - 1), xx = min(max(x, 0), W - V);
-        off[i] = (unsigned)(((size_t)yy * rowst + xx) * sizeof(T));
-        inb |= (f < TOTAL && y >= 0 && y < H && x >= 0 && x < W) ? 1u << i : 0u;
-    }
+    Fetch fetch;
+    fetch.plan(tid, x0, yb0 - R, W, H, rowst);
 
     T acc[NZ][P][V];
 #pragma unroll
@@ -350,19 +403,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     };
 
     // ---- planes straight into LDS, PF steps ahead --------------------------------------------
-    const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
-    auto request = [&](int z, int b) __attribute__((always_inline)) {
-        const bool plane_in = clamp || (z >= 0 && z < D);                     // block-uniform
-        const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
-        const unsigned keep = plane_in ? ~0u : 0u;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const char* src = pz + (off[i] & keep);
-            // zero padding: pieces outside the grid are zeros; clamp: every offset is already clamped into the grid
-            if (!clamp && (!inside_xy || (i + 1) * NTHR > TOTAL)) src = (inb >> i) & 1u ? src : zero_src;
-            load16_to_lds(src, &stage[b][i * NTHR + wave * kWave]);
-        }
-    };
+    auto request = [&](int z, int b) __attribute__((always_inline)) { fetch.request(in, plane, z, D, clamp, inside_xy, stage[b], wave); };
     // a wave that stores all P rows issues P stores per step once output planes complete (step 2R on)
     const bool full_rows = y0 + P <= H;
 #pragma unroll
@@ -371,15 +412,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     auto march = [&](auto ex) __attribute__((always_inline)) {
         int b = 0;
         for (int t = 0; t < nt; ++t) {
-            // Requests younger than those of plane t (issued at the start of step t - PF): the stores of
-            // steps t-PF .. t-1 and the loads of planes t+1 .. t+PF-1 (issued in steps t-PF+1 .. t-1).
-            int younger = 0;
-#pragma unroll
-            for (int k = 1; k <= PF; ++k) {
-                if (k < PF && t + k < nt) younger += NCH;
-                if (full_rows && t - k >= 2 * R) younger += P;
-            }
-            wait_and_sync(younger);
+            wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * R));
             // buffer (t + PF) % NBUF held plane t - 1, which every wave has finished reading
             if (t + PF < nt) request(z0 - R + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
             asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it

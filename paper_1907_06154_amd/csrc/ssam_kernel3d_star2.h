@@ -31,14 +31,11 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     constexpr int V = Piece16<T>::V;
     typedef typename Piece16<T>::type vec_t;
     constexpr int HR = 2;                      // input rows / columns / planes needed beyond the outputs, per side
-    constexpr int RS = kWave + 2;              // pieces per staged row: one halo piece per side holds the two columns
     constexpr int C = P + 2 * HR;              // input rows one wave evaluates from
-    constexpr int CB = NW * P + 2 * HR;        // rows the block stages per plane
     constexpr int L1R = P + 2, L1C = V + 2;    // first-sweep points per lane: rows y0-1 .. y0+P, columns xc-1 .. xc+V
-    constexpr int TOTAL = CB * RS;
     constexpr int NTHR = NW * kWave;
-    constexpr int NCH = (TOTAL + NTHR - 1) / NTHR;   // pieces one thread fetches per plane
-    constexpr int SLOTS = NCH * NTHR;
+    typedef PlaneFetch<T, NW * P + 2 * HR, 1, NTHR> Fetch;   // NW*P + 4 rows per plane; one halo piece per side holds the two columns
+    constexpr int RS = Fetch::RS, NCH = Fetch::NCH, SLOTS = Fetch::SLOTS;
     constexpr bool NT_STORE = (NT & kStreamStores) != 0;
     static_assert(V >= 2, "the two halo columns of a side come from one 16-byte piece");
     static_assert((PF - 1) * NCH + PF * P <= 30, "request count beyond what the wait encodes");
@@ -69,18 +66,8 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 
     const bool inside_xy = x0 - V >= 0 && x0 + (kWave + 1) * V <= W && yb0 - HR >= 0 && yb0 + NW * P + HR <= H;
 
-    // ---- this thread's pieces of the staged plane (the same for every plane) ----------------------
-    unsigned off[NCH];      // byte offset of the piece inside a plane (clamped into the grid)
-    unsigned inb = 0;       // bit i: piece i exists and lies inside the grid in x and y
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int f = i * NTHR + tid;
-        const int row = f / RS, c = f - row * RS;
-        const int y = yb0 - HR + row, x = x0 + (c - 1) * V;
-        const int yy = min(max(y, 0), H - 1), xx = min(max(x, 0), W - V);
-        off[i] = (unsigned)(((size_t)yy * rowst + xx) * sizeof(T));
-        inb |= (f < TOTAL && y >= 0 && y < H && x >= 0 && x < W) ? 1u << i : 0u;
-    }
+    Fetch fetch;
+    fetch.plan(tid, x0, yb0 - HR, W, H, rowst);
 
     // where the first sweep's points of this lane lie inside the grid (outside, the second sweep sees zero)
     unsigned colmask[L1C], rowmask[L1R];
@@ -190,18 +177,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     };
 
     // ---- planes straight into LDS, PF steps ahead (see ssam3d_star_kernel) ---------------------------
-    const char* zero_src = reinterpret_cast<const char*>(kZeroPiece);
-    auto request = [&](int z, int b) __attribute__((always_inline)) {
-        const bool plane_in = z >= 0 && z < D;                                // block-uniform
-        const char* pz = plane_in ? reinterpret_cast<const char*>(in + (size_t)min(max(z, 0), D - 1) * plane) : zero_src;
-        const unsigned keep = plane_in ? ~0u : 0u;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            const char* src = pz + (off[i] & keep);
-            if (!inside_xy || (i + 1) * NTHR > TOTAL) src = (inb >> i) & 1u ? src : zero_src;
-            load16_to_lds(src, &stage[b][i * NTHR + wave * kWave]);
-        }
-    };
+    auto request = [&](int z, int b) __attribute__((always_inline)) { fetch.request(in, plane, z, D, false, inside_xy, stage[b], wave); };
     // a wave that stores all P rows issues P stores per step once output planes complete (step 2*HR on)
     const bool full_rows = y0 + P <= H;
 #pragma unroll
@@ -209,15 +185,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         if (k < nt) request(z0 - HR + k, k);
     int b = 0;
     for (int t = 0; t < nt; ++t) {
-        // requests younger than those of plane t: the stores of steps t-PF .. t-1 and the loads of planes
-        // t+1 .. t+PF-1
-        int younger = 0;
-#pragma unroll
-        for (int k = 1; k <= PF; ++k) {
-            if (k < PF && t + k < nt) younger += NCH;
-            if (full_rows && t - k >= 2 * HR) younger += P;
-        }
-        wait_and_sync(younger);
+        wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * HR));
         if (t + PF < nt) request(z0 - HR + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
         asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it
         step(stage[b], z0 - HR + t);
