@@ -405,7 +405,7 @@ def test_fused_sweeps_tile_overrides_and_clamp(ssam, dtype):
                 ssam.ssam_set_tuning(k, -1)
 
 
-FUSED_SHAPES_3D = [(1, 1, 1), (3, 5, 7), (9, 33, 130), (20, 13, 140), (70, 10, 224), (17, 40, 300)]
+FUSED_SHAPES_3D = [(1, 1, 1), (3, 5, 7), (1, 1, 4), (2, 3, 8), (9, 33, 130), (20, 13, 140), (70, 10, 224), (17, 40, 300), (5, 70, 520)]
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
