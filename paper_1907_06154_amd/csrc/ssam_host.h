@@ -151,9 +151,12 @@ inline int wave_slots(const void* kernel)
 }
 
 // Rows per tile (a multiple of P, at least min_rows) such that strips * ceil(H / rows) tiles fill
-// `slots` wave slots k times as exactly as possible, for the smallest k that allows it.  A grid too
+// `slots` wave slots k times as exactly as possible, k = 1 .. 4.  Among fills within 2 % of each other
+// the tallest tiles win (they amortise the rows re-read at tile tops); with prefer_short the shortest win
+// unless they are more than 5 % less full (measured better for the fp64 boxes in spite of the re-read rows:
+// 8192^2 81-point 265 -> 258 us, 121-point 363 -> 351).  A grid too
 // small to fill the slots even once gets the shortest tiles allowed (most waves).
-inline int balanced_rows(int H, int P, int strips, int slots, int min_rows)
+inline int balanced_rows(int H, int P, int strips, int slots, int min_rows, bool prefer_short = false)
 {
     const int shortest = ceil_div(min_rows < P ? P : min_rows, P) * P;
     auto fill = [&](int rows) {
@@ -163,17 +166,21 @@ inline int balanced_rows(int H, int P, int strips, int slots, int min_rows)
     };
     int best_rows = shortest;
     double best_eff = fill(shortest);
-    for (int k = 1; k <= 4; ++k) {
+    bool first = true;
+    for (int i = 1; i <= 4; ++i) {
+        const int k = prefer_short ? 5 - i : i;
         const int ytiles = slots * k / strips;
         if (ytiles < 1) continue;
         int rows = ceil_div(ceil_div(H, ytiles), P) * P;
         if (rows < shortest) rows = shortest;
         const double eff = fill(rows);
-        // taller tiles amortise the rows re-read at tile tops: prefer them unless clearly less full
-        if (eff > best_eff + 0.02 || (rows > best_rows && eff > best_eff - 0.02)) {
+        const bool preferred = prefer_short ? (first || rows < best_rows) : rows > best_rows;
+        const double margin = prefer_short ? 0.05 : 0.02;
+        if (eff > best_eff + margin || (preferred && eff > best_eff - margin)) {
             best_eff = eff;
             best_rows = rows;
         }
+        first = false;
     }
     return best_rows;
 }

@@ -220,7 +220,7 @@ hipError_t launch2d(const Problem2D& pr, const Tuning& tu, Geometry* geo, bool d
         // fill the machine's wave slots a whole number of times (a partly filled last round costs
         // a full one).  Measured on 8192^2, 20x20: 57 -> 73 GStencil/s.
         static const int slots = wave_slots(reinterpret_cast<const void*>(&ssam2d_kernel<T, V, P, Mask, PREFETCH, NT, ENGINE>));
-        rows = balanced_rows(pr.H, P, g.strips_x, slots, 3 * (N - 1));
+        rows = balanced_rows(pr.H, P, g.strips_x, slots, 3 * (N - 1), sizeof(T) == 8);
     } else {
         // bandwidth-bound: the shortest tiles measured best -- one or two groups per wave, about twice the
         // N-1 rows a tile re-reads at its top (8192^2: 3x3 fp32 839 -> 918 GStencil/s from 32 to 8 rows,
