@@ -283,8 +283,9 @@ def sweep(default_json: str, vector_json: str, out_md: str) -> None:
     (the vector-unit instances of the filters whose defaults run on the matrix cores)."""
     a, v = json.load(open(default_json)), json.load(open(vector_json))
     out = ["# bench.py timing: Filter sweep 2x2 .. 20x20 (paper Sec. 6.2), 8192x8192 fp32, clamp\n",
-           "One MI355X, HIP events on the launch stream, medians per launch; the input is one tensor (warm in the memory-side "
-           "cache; `bench.py` without arguments reports the configuration-2 filters cold).  Second run: tuning variant 5, the "
+           "One MI355X, HIP events on the launch stream, medians per launch; every launch reads a different one of four copies "
+           "of the image, so nothing it reads is resident in the memory-side cache (cold, as in `bench.py` without arguments).  "
+           "Second run: tuning variant 5, the "
            "vector-unit instances of the filters whose default instances (`...mx`) evaluate their products on the matrix cores "
            "(shapes without such an alternative run their default in both).\n",
            f"    python bench.py --workload filter_sweep --no-cpu-baseline --steps {a['steps']} --warmup {a['warmup']} > {default_json}\n"
