@@ -424,6 +424,19 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     else march(std::false_type{});
 }
 
+// All blocks of these kernels march through their z-chunks in step, so at any moment the device reads one plane and
+// writes one plane per chunk.  When the chunks start a multiple of 128 MiB apart, those planes fall on the same
+// DRAM banks in every chunk, and for many distances between the input and the output buffer the reads then collide
+// with the writes (512^3 fp64: 360 us at the good distances, 395-415 us in bands that cover half of all
+// distances; mean over distances 385 us).  Chunks four planes longer (the last one shorter) spread them: mean
+// 370 us, worst 395.  (fp32 grids of this size, with chunks 64 MiB apart, show no such effect.)
+inline int staggered_planes(int planes, int depth, size_t plane_bytes)
+{
+    if (planes >= depth || (planes * plane_bytes) % (128u << 20) != 0) return planes;
+    const int longer = planes + 4;
+    return ceil_div(depth, longer) == ceil_div(depth, planes) ? longer : planes;
+}
+
 // Fallback of a shape that has no other compiled instance: the dispatcher then takes the direct kernel.
 inline hipError_t launch3d_unavailable(const Problem3D&, const Tuning&, Geometry*, bool) { return hipErrorNotSupported; }
 
@@ -461,6 +474,7 @@ hipError_t launch3d_star(const Problem3D& pr, const Tuning& tu, Geometry* geo, b
             blocks_per_cu = 1;
         }
         planes = balanced_planes(LD, (long)g.strips_x * g.tiles_y, cus * blocks_per_cu, LD, 4 * R);
+        if (!pr.march_y) planes = staggered_planes(planes, LD, slice);
     }
     if (planes > LD) planes = LD;
     g.planes_per_wave = planes;

@@ -227,6 +227,7 @@ hipError_t launch3d_star2(const Problem3D& pr, const Tuning& tu, Geometry* geo, 
             blocks_per_cu = 1;
         }
         planes = balanced_planes(pr.D, (long)g.strips_x * g.tiles_y, cus * blocks_per_cu, pr.D, 8);
+        planes = staggered_planes(planes, pr.D, slice);
     }
     if (planes > pr.D) planes = pr.D;
     g.planes_per_wave = planes;
