@@ -516,14 +516,18 @@ __device__ __forceinline__ void systolic_rows_mfma(const Rows& r, const float* t
 #pragma unroll
     for (int j = 0; j < V; ++j) have[j] = gl[j] = gr[j] = false;
     float a[2][CP];
+    typedef __attribute__((address_space(3))) const float lds_float;
+    lds_float* col = (lds_float*)tab_lane;         // the table lives in LDS
 
     auto request = [&](auto tt) __attribute__((always_inline)) {
         constexpr int t = decltype(tt)::value;
         constexpr MfmaJob jb = Plan::list.job[t];
-        const float* col = tab_lane + opaque_zero();
+        // the table pointer passes through an empty asm statement: the compiler cannot see through it, so the reads
+        // of this job stay here, and no instruction is spent (the same register carries on to the next job)
+        asm volatile("" : "+v"(col));
 #pragma unroll
         for (int k = 0; k < CP; k += 4) {
-            const v4f piece = *reinterpret_cast<const v4f*>(col + jb.m * 4 * CP + k);
+            const v4f piece = *reinterpret_cast<__attribute__((address_space(3))) const v4f*>(col + jb.m * 4 * CP + k);
 #pragma unroll
             for (int e = 0; e < 4; ++e) a[t & 1][k + e] = piece[e];
         }
