@@ -7,6 +7,7 @@ profiles/measured_traffic.json, the HBM bytes per launch that bench.py reports a
     python -m paper_1907_06154_amd.profiling resources <out.md>
     python -m paper_1907_06154_amd.profiling catalogue <single.json> <default.json> <out.md>
     python -m paper_1907_06154_amd.profiling sweep <default.json> <variant5.json> <out.md>
+    python -m paper_1907_06154_amd.profiling scan <dir> <out.md>
 
 `summarize` expects three rocprofv3 runs of the same bench.py command (the commands are written
 into the summary), each with its bench.py output saved beside it:
@@ -38,7 +39,9 @@ TRAFFIC = os.path.join(ROOT, "profiles", "measured_traffic.json")
 
 
 def short(name: str) -> str:
-    name = name.replace("void ssam::", "").replace("ssam::(anonymous namespace)::", "")
+    for prefix in ("void ", "ssam::", "(anonymous namespace)::"):
+        if name.startswith(prefix):
+            name = name[len(prefix):]
     return name.split("(ssam::")[0].split("(HIP_vector")[0].split("(float")[0].split("(double")[0]
 
 
@@ -307,6 +310,60 @@ def sweep(default_json: str, vector_json: str, out_md: str) -> None:
     print("\n".join(out))
 
 
+def scan_summary(prefix: str, out_md: str) -> None:
+    """The scan: <prefix>/<tag>_{trace,fetch,write}/ (rocprofv3 output) and <prefix>/<tag>_trace.txt (what the traced
+    bench.py --tune run printed), tag = f32, f64; both schedules of the 1 GiB arrays in every run."""
+    out = ["# rocprofv3 summary: inclusive scan (ssam_scan), 1 GiB arrays: 2^28 fp32 and 2^27 fp64 elements, both schedules\n",
+           "Both schedules are timed by the same command (`scan_chained=0`: three launches, `scan_chained=1`: one pass, the "
+           "default at this size), followed by the plain copy kernel on the same arrays.\n"]
+    traffic = load_traffic()
+    for tag, n, tname in (("f32", 1 << 28, "float"), ("f64", 1 << 27, "double")):
+        cmd = f'python3 bench.py --workload scan --cases {tag}:{n} --tune "scan_chained=0,1"'
+        out.append(f"## {tag}, n = {n}\n\nKernel durations:\n")
+        out.append(f"    rocprofv3 --kernel-trace --stats --output-format csv -d {prefix}/{tag}_trace -o c -- {cmd}\n")
+        out.append("From the kernel trace of that run; `scan_one_group` is the one-workgroup fallback enqueued behind every "
+                   "one-pass call; it returns at once unless a wave gave up (never in these runs):\n")
+        out.append("| kernel | dispatches | avg us | min us | max us |\n|---|---|---|---|---|")
+        for r in csv.DictReader(open(one(os.path.join(prefix, tag + "_trace", "**", "*kernel_stats.csv")))):
+            if ours(r["Name"]) or is_copy(r["Name"]):
+                out.append(f"| `{short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | "
+                           f"{float(r['MinNs']) / 1e3:.1f} | {float(r['MaxNs']) / 1e3:.1f} |")
+        out.append("\nThe same run's HIP-event timing per call (all launches of the call; algorithmic bytes = one read + one "
+                   "write per element):\n\n```")
+        out += [l.rstrip() for l in open(os.path.join(prefix, tag + "_trace.txt")) if l.startswith(("scan ", "copy "))]
+        out.append("```\n\nHBM traffic counters (each in a run of its own; KiB per dispatch, mean over dispatches):\n")
+        per = {}
+        copy = {}
+        for kind, ctr in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+            out.append(f"    rocprofv3 --pmc {ctr} --kernel-trace --output-format csv -d {prefix}/{tag}_{kind} -o c -- {cmd}")
+            for k, c, _ in counter_dispatches(os.path.join(prefix, f"{tag}_{kind}")):
+                if is_copy(k):
+                    copy.setdefault(kind, []).append(c[ctr])
+                elif k.startswith("scan_"):
+                    per.setdefault(k, {"fetch": [], "write": []})[kind].append(c[ctr])
+        array_kib = (1 << 30) / 1024.0
+        scale = {kind: array_kib / (sum(v) / len(v)) for kind, v in copy.items()}
+        out.append(f"\nThe plain copy kernel (`ssam_probe_copy`, 1024 MiB read and written) reads FETCH_SIZE = "
+                   f"{sum(copy['fetch']) / len(copy['fetch']):.0f} KiB and WRITE_SIZE = {sum(copy['write']) / len(copy['write']):.0f} "
+                   f"KiB: scale factors {scale['fetch']:.3f} (fetch) and {scale['write']:.3f} (write).\n")
+        out.append("| kernel | dispatches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled read MiB | scaled write MiB | "
+                   "read+write / array size |\n|---|---|---|---|---|---|---|")
+        for k, v in per.items():
+            f = sum(v["fetch"]) / max(1, len(v["fetch"]))
+            w = sum(v["write"]) / max(1, len(v["write"]))
+            tot = (f * scale["fetch"] + w * scale["write"]) / 1024
+            out.append(f"| `{k}` | {len(v['fetch'])} | {f:.0f} | {w:.0f} | {f * scale['fetch'] / 1024:.1f} | "
+                       f"{w * scale['write'] / 1024:.1f} | {tot / 1024:.3f} |")
+            if k.startswith("scan_chained"):
+                key = f"scan_chained_{tag}@{n}"
+                traffic["bytes_per_launch"][key] = int(tot * 2 ** 20)
+                traffic["source"][key] = os.path.relpath(out_md, ROOT)
+        out.append("")
+    open(out_md, "w").write("\n".join(out) + "\n")
+    json.dump(traffic, open(TRAFFIC, "w"), indent=1, sort_keys=True)
+    print("\n".join(out))
+
+
 def main(argv) -> int:
     if len(argv) >= 3 and argv[0] == "summarize":
         title = argv[argv.index("--title") + 1]
@@ -320,6 +377,8 @@ def main(argv) -> int:
         catalogue(argv[1], argv[2], argv[3])
     elif len(argv) == 4 and argv[0] == "sweep":
         sweep(argv[1], argv[2], argv[3])
+    elif len(argv) == 3 and argv[0] == "scan":
+        scan_summary(argv[1], argv[2])
     elif len(argv) == 2 and argv[0] == "resources":
         resources(argv[1])
     else:
