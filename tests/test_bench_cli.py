@@ -28,7 +28,7 @@ def test_measured_traffic_file_is_what_bench_expects():
         points = 1
         for d in dims:
             points *= d
-        esz = 8 if inst.startswith("double") else 4
+        esz = 8 if inst.startswith("double") or inst.endswith("_f64") else 4
         assert 0.99 * 2 * esz * points <= entry <= 1.3 * 2 * esz * points, key
 
 
