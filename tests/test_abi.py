@@ -290,6 +290,31 @@ def test_fused_sweep_plan(L):
     assert parse(ssam.ssam_describe("iterate2d", (512, 512), wide, "zero"))[0] == "generic_direct"
 
 
+def test_block_cooperative_3d_plans(L):
+    """The block-cooperative 3D kernels: every lane stores, one block per compute unit on 512^3, and z-chunks that
+    would start a multiple of 128 MiB apart are made four planes longer (the last one shorter)."""
+    for dtype, r, planes in ((np.float64, 1, 132), (np.float64, 4, 260), (np.float32, 1, 64), (np.float32, 4, 132)):
+        coef = wl.seeded_coefficients(wl.mask_star(r, r, r), 1, dtype)
+        name, g = parse(ssam.ssam_describe("stencil3d", (512, 512, 512), coef, "zero"))
+        assert "star_ring" in name and g["halo_lanes"] == 0 and g["valid_lanes"] == 64
+        assert g["planes_per_wave"] == planes and g["tiles"] == 256
+        assert g["tiles_z"] == -(-512 // planes)
+    # a chunk spacing that is no multiple of 128 MiB stays as it is
+    coef = wl.seeded_coefficients(wl.mask_star(1, 1, 1), 1, np.float64)
+    assert parse(ssam.ssam_describe("stencil3d", (256, 256, 256), coef, "zero"))[1]["planes_per_wave"] == 16
+
+
+def test_fp64_arithmetic_bound_filters_take_short_balanced_tiles(L):
+    for r in (4, 5):
+        coef = wl.seeded_coefficients(wl.mask_box(r, r), 1, np.float64)
+        coef = coef[0] if coef.ndim == 3 else coef
+        name, g = parse(ssam.ssam_describe("stencil2d", (8192, 8192), coef, "zero"))
+        assert name.startswith("double_M") and g["rows_per_wave"] <= 64
+    # the fp32 ones keep the tallest balanced tiles
+    name, g = parse(ssam.ssam_describe("conv2d", (8192, 8192), np.ones((20, 20), np.float32), "clamp"))
+    assert name.endswith("mx") and g["rows_per_wave"] >= 64
+
+
 def test_fused_sweep_plan_3d(L):
     """Radius-1 3D stencils with zero padding run two sweeps per launch when marching along z (one wave per
     tile: two incomplete columns per side; the 7-point star: block-cooperative, no incomplete lanes); radius 4
