@@ -38,6 +38,13 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} not found: build it with `python -m paper_1907_06154_amd.build` "
                 "(there is no fallback implementation)")
+        # A process can drive the GPU through ONE HIP runtime.  torch brings its own copy; if this library
+        # were loaded first it would bind to the system's copy, and whichever of the two initialises second
+        # finds no device (every launch then returns SSAM_ERR_HIP).  Loading torch first makes both share torch's.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
         L.ssam_conv2d.argtypes = [vp, vp, ci, ci, vp, ci, ci, ci, ci, ci, ci, vp]
