@@ -1,6 +1,8 @@
 """Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
 public header declares, validates its arguments before any GPU call, and plans tile
-geometry as the design states.  No compute call is made here."""
+geometry as the design states.  Every call that is given made-up pointers fails validation
+before anything is launched, so the file is safe to run on a machine with a GPU as well (where
+the one call that passes validation gets real device memory)."""
 import ctypes
 import os
 import re
