@@ -19,7 +19,7 @@ events around its launches inside the timed region), "kernels", "parity" (the GP
 configuration-2 case compared in this process with the field the CPU oracle computes for the
 "cpu_baseline" leg) and "cpu_baseline" (the oracle timed on a bounded sample).
 
-Other workloads: --workload config1 .. config5, filter_sweep, table3 (a step is then the whole
+Other workloads: --workload config1 .. config5, filter_sweep, table3, conv3d (a step is then the whole
 configuration: every case, all its sweeps), scan.  --tune "<knob>=v1,v2;<knob2>=..." times the
 selected cases under every combination of tuning overrides (ssam_set_tuning) instead, one after the
 other in this process (the clock differs between processes and boxes by several per cent, so variants
@@ -84,6 +84,8 @@ class Timer:
 def run_single(ssam, case, d_in, d_out):
     if case.kind == "conv2d":
         ssam.ssam_conv2d(d_in, case.coef, case.boundary, d_out=d_out)
+    elif case.kind == "conv3d":
+        ssam.ssam_conv3d(d_in, case.coef, case.boundary, d_out=d_out)
     elif case.kind == "stencil2d":
         ssam.ssam_stencil2d(d_in, case_coef(case), case.boundary, d_out=d_out)
     else:
@@ -221,6 +223,8 @@ def cpu_baseline_and_parity(ssam, torch, cases, outputs, target_seconds: float):
         t0 = time.perf_counter()
         if case.kind == "conv2d":
             res = oracle.conv2d(sample, case.coef, case.boundary)
+        elif case.kind == "conv3d":
+            res = oracle.conv3d(sample, case.coef, case.boundary)
         else:
             res = oracle.stencil(sample, case_coef(case), case.boundary)
         return time.perf_counter() - t0, int(np.prod(shape)), res
@@ -619,7 +623,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="default",
-                    choices=["default", "config1", "config2", "config3", "config4", "config5", "filter_sweep", "table3", "scan"])
+                    choices=["default", "config1", "config2", "config3", "config4", "config5", "filter_sweep", "table3", "conv3d", "scan"])
     ap.add_argument("--cases", default=None, help="comma-separated substrings selecting cases of the workload")
     ap.add_argument("--fuse-sweeps", type=int, default=-1,
                     help="cap on the sweeps ssam_stencil_iterate fuses into one launch (0: none; default: the library's choice)")

@@ -44,6 +44,9 @@ def reach_of(case):
         N, M = case.coef.shape
         ax, ay = M // 2, N // 2
         return (ay, ax), (N - 1 - ay, M - 1 - ax)
+    if case.kind == "conv3d":
+        lo = tuple(s // 2 for s in case.coef.shape)                 # centre anchor per axis
+        return lo, tuple(s - 1 - a for s, a in zip(case.coef.shape, lo))
     r = [s // 2 * case.steps for s in case.coef.shape]
     if case.kind == "stencil2d":
         r = r[1:]
@@ -57,6 +60,8 @@ def oracle_window(case, lo, hi):
     import oracle
     if case.kind == "conv2d":
         full = oracle.conv2d(crop, case.coef, case.boundary)
+    elif case.kind == "conv3d":
+        full = oracle.conv3d(crop, case.coef, case.boundary)
     else:
         coef = case.coef if case.kind == "stencil3d" else case.coef[0]
         full = oracle.iterate(crop, coef, case.steps, case.boundary)

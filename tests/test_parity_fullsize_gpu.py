@@ -44,6 +44,8 @@ def run_gpu(ssam, case):
     b = torch.empty_like(a)
     if case.kind == "conv2d":
         res = ssam.ssam_conv2d(a, case.coef, case.boundary, d_out=b)
+    elif case.kind == "conv3d":
+        res = ssam.ssam_conv3d(a, case.coef, case.boundary, d_out=b)
     else:
         coef = case.coef if case.kind == "stencil3d" else case.coef[0]
         res = ssam.ssam_stencil_iterate(a, b, coef, case.steps, case.boundary)
@@ -110,6 +112,13 @@ def test_config4_full_size_10_sweeps(ssam, case):
 def test_config5_full_size_20_sweeps(ssam, case):
     wins = windows_3d(512, 12)
     check(ssam, case, [wins[0], wins[1], wins[3], wins[4]])
+
+
+@pytest.mark.parametrize("case", wl.conv3d_filters(), ids=lambda c: c.name)
+def test_conv3d_full_size(ssam, case):
+    """The 512^3 dense 3D filters that bench.py --workload conv3d times: cubes with an instance of their own,
+    an even cube and a flat box that run inside a larger cube."""
+    check(ssam, case, windows_3d(512, 20))
 
 
 def test_full_size_run_is_deterministic(ssam):

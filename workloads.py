@@ -172,12 +172,12 @@ def seeded_filter(M: int, N: int, seed: int, dtype, lo: float = -1.0, hi: float 
 class Case:
     """One (grid, coefficients, boundary, steps) problem instance."""
     name: str
-    kind: str                 # "conv2d" | "stencil2d" | "stencil3d"
+    kind: str                 # "conv2d" | "conv3d" | "stencil2d" | "stencil3d"
     dtype: type
     shape: Tuple[int, ...]    # (H, W) or (D, H, W)
     field_range: Tuple[float, float]
     field_seed: int
-    coef: np.ndarray          # conv2d: [N][M]; stencils: [2rz+1][2ry+1][2rx+1]
+    coef: np.ndarray          # conv2d: [N][M]; conv3d: [K][N][M]; stencils: [2rz+1][2ry+1][2rx+1]
     boundary: str             # "zero" | "clamp"
     steps: int
     paper_analogue: str = ""
@@ -275,6 +275,21 @@ def table3(n2: int = 8192, n3: int = 512, steps: int = 10, dtypes=(np.float32, n
     return out
 
 
+def conv3d_filters(n: int = 512) -> List[Case]:
+    """Dense 3D filters (the mapping the paper names as its next one, Sec. 6 opening paragraph and Sec. 8) on an
+    n^3 volume, clamp, one pass: the cubes 3^3, 5^3 and 7^3 in fp32, 3^3 in fp64, and two shapes that are not
+    cubes of odd extent (4x4x4, centre anchor 2; 5x3x2 = M x N x K), which run inside the smallest cube that holds them."""
+    out = []
+    for i, (M, N, K, dt) in enumerate([(3, 3, 3, np.float32), (5, 5, 5, np.float32), (7, 7, 7, np.float32),
+                                       (4, 4, 4, np.float32), (5, 3, 2, np.float32), (3, 3, 3, np.float64)]):
+        tag = "f32" if dt == np.float32 else "f64"
+        filt = uniform_field((K, N, M), -1.0, 1.0, 400 + i, dt)
+        out.append(Case(f"c3d_conv{M}x{N}x{K}_{tag}", "conv3d", dt, (n, n, n), (0.0, 1.0), 8, filt, "clamp", 1,
+                        "3D convolution (Sec. 8, future work)"))
+    return out
+
+
 def all_configs() -> Dict[str, List[Case]]:
     return {"config1": config1(), "config2": config2(), "config3": config3(),
-            "config4": config4(), "config5": config5(), "filter_sweep": filter_sweep(), "table3": table3()}
+            "config4": config4(), "config5": config5(), "filter_sweep": filter_sweep(), "table3": table3(),
+            "conv3d": conv3d_filters()}
