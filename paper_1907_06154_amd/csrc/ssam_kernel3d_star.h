@@ -243,47 +243,78 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     // cut the unrolled step into short basic blocks (7x7x7 box, fp32, 512^3, every block at an edge: 1.83 ms with
     // branches, 1.61 ms without, against 1.52 ms under zero padding).
     const bool beyond_r = clamp_r && beyond;
-    int edge_of_own = clamp_r ? last_piece : own;    // the piece whose last column the lanes beyond the grid repeat
-    asm volatile("" : "+v"(edge_of_own));            // opaque, or the compiler branches around its read in every row
-    auto own_piece = [&](auto ex, const vec_t* st, int k) __attribute__((always_inline)) {
+    // the lane whose piece ends in column W-1 (meaningful when clamp_r)
+    const int last_lane = __builtin_amdgcn_readfirstlane(min(max((W - x0) / V - 1, 0), kWave - 1));
+    // Each selection is a read (possibly from a selected address) and a fix of the value read, so that a step can
+    // request all its pieces first and fix them afterwards.
+    auto read_own = [&](const vec_t* st, int k) __attribute__((always_inline)) { return st[own + k * RS]; };
+    auto fix_own = [&](auto ex, vec_t v) __attribute__((always_inline)) {
         if constexpr (decltype(ex)::value) {
-            const vec_t v = st[own + k * RS];
-            const vec_t e = st[edge_of_own + k * RS];
-            vec_t r;
+            // lanes beyond the grid repeat column W-1, which the lane last_lane has just read: a lane broadcast,
+            // no second LDS read
+            const T e = read_lane((T)v[V - 1], last_lane);
 #pragma unroll
-            for (int j = 0; j < V; ++j) r[j] = beyond_r ? e[V - 1] : v[j];
-            return r;
-        } else {
-            return st[own + k * RS];
+            for (int j = 0; j < V; ++j) v[j] = beyond_r ? e : v[j];
         }
+        return v;
     };
-    auto left_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+    auto read_left = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        // under the rule the row's first column repeated: its piece is the first after the halo.  Without it the
+        // halo piece itself (the same address in every lane: a broadcast)
+        if constexpr (decltype(ex)::value) return st[edge_l + k * RS + (clamp_l ? HC : HC - h)];
+        else return st[edge_l + k * RS + (HC - h)];
+    };
+    auto fix_left = [&](auto ex, vec_t v) __attribute__((always_inline)) {
         if constexpr (decltype(ex)::value) {
-            // under the rule the row's first column repeated: its piece is the first after the halo
-            vec_t v = st[edge_l + k * RS + (clamp_l ? HC : HC - h)];
 #pragma unroll
             for (int j = 1; j < V; ++j) v[j] = clamp_l ? v[0] : v[j];
-            return v;
-        } else {
-            return st[edge_l + k * RS + (HC - h)];   // same address in every lane: a broadcast
         }
+        return v;
     };
-    auto right_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+    auto read_right = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        if constexpr (decltype(ex)::value) return st[(h > right_in ? last_piece : edge_r + (h - 1)) + k * RS];
+        else return st[edge_r + k * RS + (h - 1)];
+    };
+    auto fix_right = [&](auto ex, vec_t v, int h) __attribute__((always_inline)) {
         if constexpr (decltype(ex)::value) {
             const bool outside = h > right_in;       // block-uniform
-            vec_t v = st[(outside ? last_piece : edge_r + (h - 1)) + k * RS];
 #pragma unroll
             for (int j = 0; j < V - 1; ++j) v[j] = outside ? v[V - 1] : v[j];
-            return v;
-        } else {
-            return st[edge_r + k * RS + (h - 1)];
         }
+        return v;
+    };
+    auto own_piece = [&](auto ex, const vec_t* st, int k) __attribute__((always_inline)) { return fix_own(ex, read_own(st, k)); };
+    auto left_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        return fix_left(ex, read_left(ex, st, k, h));
+    };
+    auto right_piece = [&](auto ex, const vec_t* st, int k, int h) __attribute__((always_inline)) {
+        return fix_right(ex, read_right(ex, st, k, h), h);
     };
 
     // one step of the march: the staged plane `st` is input plane zin
     auto step = [&](auto ex, const vec_t* st, int zin) __attribute__((always_inline)) {
         if constexpr (BUDGET == 1) {
             T sum[P][V];       // in-plane sums, seeded with the plane above's partial sums
+            // every piece the step reads is requested before anything is computed from it: one wait for all of them
+            vec_t rowv[C], hl[P][HC], hr[P][HC];
+#pragma unroll
+            for (int k = 0; k < C; ++k) rowv[k] = read_own(st, k);
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int h = 1; h <= HC; ++h) {
+                    hl[p][h - 1] = read_left(ex, st, p + R, h);
+                    hr[p][h - 1] = read_right(ex, st, p + R, h);
+                }
+            if constexpr (decltype(ex)::value) {
+                __builtin_amdgcn_sched_barrier(0);
+                // one block-uniform branch per step: this kernel has few instructions per step to hide the fixes
+                // behind (radius 4, 512^3: 15 % when every edge block made them, needed or not)
+                if (clamp_r) {
+#pragma unroll
+                    for (int k = 0; k < C; ++k) rowv[k] = fix_own(ex, rowv[k]);
+                }
+            }
             // -- per window: z taps and the centre tap (in-flight plane s takes dz = R - s from this
             //    input plane), then the x taps: neighbouring columns of the centre row, shifted in
             //    from the lanes beside (the columns beyond the wave's own come in as the edge lanes'
@@ -291,7 +322,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
             for (int p = 0; p < P; ++p) {
                 T xs[(2 * HC + 1) * V];     // columns -HC*V .. (HC+1)*V - 1 relative to the lane's first
-                const vec_t v = own_piece(ex, st, p + R);
+                const vec_t v = rowv[p + R];
 #pragma unroll
                 for (int j = 0; j < V; ++j) xs[HC * V + j] = v[j];
                 const T* cen = &xs[HC * V];
@@ -309,8 +340,8 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
                 for (int j = 0; j < V; ++j) acc[NZ - 1][p][j] = cen[j] * wts[0];
 #pragma unroll
                 for (int h = 1; h <= HC; ++h) {
-                    const vec_t el = left_piece(ex, st, p + R, h);
-                    const vec_t er = right_piece(ex, st, p + R, h);
+                    const vec_t el = fix_left(ex, hl[p][h - 1]);
+                    const vec_t er = fix_right(ex, hr[p][h - 1], h);
 #pragma unroll
                     for (int j = 0; j < V; ++j) {
                         xs[(HC - h) * V + j] = shift_in_up(xs[(HC - h + 1) * V + j], (T)el[j]);
@@ -328,7 +359,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             // -- y taps: every staged row of the wave's window
 #pragma unroll
             for (int k = 0; k < C; ++k) {
-                const vec_t v = own_piece(ex, st, k);
+                const vec_t v = rowv[k];
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     const int dy = k - R - p;
@@ -431,7 +462,11 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             b = b + 1 == NBUF ? 0 : b + 1;
         }
     };
+#ifdef SSAM_X1
+    if (false) march(std::true_type{});
+#else
     if (clamp_l || clamp_r || right_in < HC) march(std::true_type{});   // block-uniform
+#endif
     else march(std::false_type{});
 }
 
