@@ -462,11 +462,7 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             b = b + 1 == NBUF ? 0 : b + 1;
         }
     };
-#ifdef SSAM_X1
-    if (false) march(std::true_type{});
-#else
     if (clamp_l || clamp_r || right_in < HC) march(std::true_type{});   // block-uniform
-#endif
     else march(std::false_type{});
 }
 
