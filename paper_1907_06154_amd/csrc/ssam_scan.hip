@@ -64,13 +64,11 @@ constexpr int kOffsetsEach = kScanMaxSegments / kOffsetsThreads;   // ... and th
 // 26 KiB for fp64 (the most that fits 256 registers, two waves per SIMD -- fewer, longer segments
 // measured faster than more waves), 16 KiB with element-wise accesses.  The workspace is sized for
 // the shortest segments.
-#if !defined(SSAM_SCAN_ROUNDS_F64)
-#define SSAM_SCAN_ROUNDS_F64 26
-#endif
+constexpr int kChainRoundsF64 = 26;
 constexpr int kChainRoundsUnaligned = 16;
 constexpr int chain_rounds(int dtype, bool aligned)
 {
-    return !aligned ? kChainRoundsUnaligned : dtype == SSAM_F32 ? 32 : SSAM_SCAN_ROUNDS_F64;
+    return !aligned ? kChainRoundsUnaligned : dtype == SSAM_F32 ? 32 : kChainRoundsF64;
 }
 constexpr int kChainFan = 64;                                      // items summed per level = lanes
 constexpr long long kChainMaxSegments = 64LL * 64 * 64;            // three levels
