@@ -234,17 +234,32 @@ def resources(out_md: str, only_default: bool = True) -> None:
                 continue
             if m.group(1) == "Function Name":
                 name = subprocess.run(["c++filt", m.group(2)], capture_output=True, text=True).stdout.strip()
-                cur = {"file": os.path.basename(src), "kernel": short(name)}
+                cur = {"file": os.path.basename(src), "src": src, "mangled": m.group(2), "kernel": short(name)}
                 rows.append(cur)
             elif cur is not None:
                 cur[m.group(1).split(" [")[0]] = m.group(2)
+    # A private segment can be reserved without ever being used (slots of scalar-register spills that ended up in
+    # vector-register lanes): for the kernels that report one, count the scratch instructions in the assembly.
+    for src in sorted({r["src"] for r in rows if r.get("ScratchSize", "0") != "0"}):
+        asm = subprocess.run(["hipcc", *flags, "--cuda-device-only", "-S", src, "-o", "-"], capture_output=True, text=True)
+        if asm.returncode != 0:
+            raise SystemExit(asm.stderr)
+        for body in re.split(r"\n\t\.type\t", asm.stdout)[1:]:
+            mangled = body.split(",")[0]
+            for r in rows:
+                if r.get("mangled") == mangled:
+                    r["scratch_instructions"] = len(re.findall(r"\bscratch_(?:load|store)", body))
+    spilled = [r for r in rows if r.get("ScratchSize", "0") != "0"]
     out = ["# Registers, LDS and scratch of every compiled kernel (gfx950)\n",
            "From the compiler's resource report, no GPU involved:\n",
            "    python -m paper_1907_06154_amd.profiling resources profiles/kernel_resources.md\n",
            "(`hipcc --offload-arch=gfx950 -O3 ... --cuda-device-only -Rpass-analysis=kernel-resource-usage` per translation unit.)  "
            "VGPRs + AGPRs share one file of 512 registers per SIMD lane: waves per SIMD = floor(512 / (VGPRs + AGPRs, rounded up "
-           "to 8)), at most 8; a block's LDS also limits the blocks per compute unit (160 KiB).  Kernels with scratch (register "
-           "spills): " + (", ".join(f"`{r['kernel']}` ({r.get('ScratchSize')} bytes per lane)" for r in rows if r.get("ScratchSize", "0") != "0") or "none") + ".\n",
+           "to 8)), at most 8; a block's LDS also limits the blocks per compute unit (160 KiB).  Kernels for which the compiler "
+           "reserves a private segment (bytes per lane; scratch loads and stores in their code): "
+           + (", ".join(f"`{r['kernel']}` ({r.get('ScratchSize')}; {r.get('scratch_instructions', '?')})" for r in spilled) or "none")
+           + ".  A reserved segment without scratch instructions is never touched: its slots belonged to scalar-register "
+           "spills that ended up in vector-register lanes.\n",
            "| translation unit | kernel | VGPRs | AGPRs | SGPRs | LDS bytes / block | scratch bytes / lane | waves / SIMD |\n|---|---|---|---|---|---|---|---|"]
     for r in rows:
         out.append(f"| {r['file']} | `{r['kernel']}` | {r.get('VGPRs', '')} | {r.get('AGPRs', '')} | {r.get('TotalSGPRs', '')} | "
