@@ -42,3 +42,21 @@ def test_every_profile_summary_names_the_command_that_made_it():
             assert "_work/" not in c and "tune.py" not in c, (os.path.basename(path), c)
             for module in re.findall(r"python -m paper_1907_06154_amd\.(\w+)", c):
                 assert os.path.exists(os.path.join(ROOT, "paper_1907_06154_amd", module + ".py")), (os.path.basename(path), c)
+
+
+def test_every_workload_of_the_generators_can_be_named_on_the_command_line():
+    """bench.py --workload accepts every key of workloads.all_configs() (plus the default line and the scan)."""
+    sys.path.insert(0, ROOT)
+    import workloads as wl
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0
+    choices = re.search(r"--workload \{([^}]*)\}", res.stdout.replace("\n", " "))
+    assert choices, res.stdout
+    names = {c.strip() for c in choices.group(1).split(",")}
+    assert set(wl.all_configs()) | {"default", "scan"} == names, names
+    for cases in wl.all_configs().values():
+        assert len({c.name for c in cases}) == len(cases)          # case names are unique within a workload
+        for c in cases:
+            assert c.kind in ("conv2d", "conv3d", "stencil2d", "stencil3d"), c.name
+            assert c.coef.ndim == (2 if c.kind == "conv2d" else 3), c.name
+            assert len(c.shape) == (2 if c.kind in ("conv2d", "stencil2d") else 3), c.name
