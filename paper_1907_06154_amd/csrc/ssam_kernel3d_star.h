@@ -454,7 +454,15 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     auto march = [&](auto ex) __attribute__((always_inline)) {
         int b = 0;
         for (int t = 0; t < nt; ++t) {
-            wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * R));
+            // Away from both ends of the chunk the count is one of two constants; naming them spares every step the
+            // chain of compares and branches that picks the wait's immediate.
+            constexpr int kSteadyLoads = (PF - 1) * NCH, kSteadyAll = kSteadyLoads + PF * P;
+            if (t >= 2 * R + PF && t + PF <= nt) {
+                if (full_rows) wait_and_sync_n<(kSteadyAll & ~1)>();
+                else wait_and_sync_n<(kSteadyLoads & ~1)>();
+            } else {
+                wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * R));
+            }
             // buffer (t + PF) % NBUF held plane t - 1, which every wave has finished reading
             if (t + PF < nt) request(z0 - R + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
             asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it
