@@ -185,7 +185,14 @@ __global__ __launch_bounds__(NW* kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         if (k < nt) request(z0 - HR + k, k);
     int b = 0;
     for (int t = 0; t < nt; ++t) {
-        wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * HR));
+        // away from both ends of the chunk the count is one of two constants (as in ssam3d_star_kernel)
+        constexpr int kSteadyLoads = (PF - 1) * NCH, kSteadyAll = kSteadyLoads + PF * P;
+        if (t >= 2 * HR + PF && t + PF <= nt) {
+            if (full_rows) wait_and_sync_n<(kSteadyAll & ~1)>();
+            else wait_and_sync_n<(kSteadyLoads & ~1)>();
+        } else {
+            wait_and_sync(younger_requests<PF, NCH, P>(t, nt, full_rows, 2 * HR));
+        }
         if (t + PF < nt) request(z0 - HR + t + PF, b + PF >= NBUF ? b + PF - NBUF : b + PF);
         asm volatile("" ::: "memory");   // the step's stores stay behind its requests: the count above relies on it
         step(stage[b], z0 - HR + t);
